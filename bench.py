@@ -1,0 +1,165 @@
+#!/usr/bin/env python3
+"""Benchmark of the PSO-PS synchronization step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+A step is one whole synchronization stage (selection + fused update) of the
+named swarm, whose state is resident in HBM before the timed region starts.
+Prints ONE JSON line: whole-job particle-parameters per second, the HBM
+roofline of the update kernel measured live with events on the launch stream,
+and the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import hashlib
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
+
+# HBM bytes per update-kernel launch from rocprofv3 --pmc runs (FETCH_SIZE and
+# WRITE_SIZE, each scaled by what the counter reads for a plain copy of known
+# size), keyed by workload and by the hash of the kernel source they were taken
+# with: a changed kernel reports null until the counters are taken again.
+MEASURED_TRAFFIC = {}
+
+
+def kernel_source_hash() -> str:
+    from paper_2009_03816_amd import build
+    with open(build.SOURCE, "rb") as f:
+        return hashlib.sha256(f.read()).hexdigest()[:16]
+
+
+def cpu_baseline(cfg, seconds_target: float = 12.0):
+    """The oracle as it stands, single-threaded, on the first columns of the
+    same swarm: one stage, sized for roughly `seconds_target` of CPU work."""
+    import numpy as np
+    from oracle import pso_ps_oracle as oracle
+    from paper_2009_03816_amd import workloads as wl
+
+    oracle.build()
+    rate_guess = 25e6                                   # elements/s, order of magnitude only
+    n = int(min(cfg.D, max(1024, seconds_target * rate_guess / cfg.K)))
+    n -= n % 2
+    rng = np.random.default_rng(cfg.seed)
+    losses = wl.draw_losses(cfg, rng, 2)
+    x = (rng.standard_normal((cfg.K, n), dtype=np.float32) * np.float32(cfg.x_sigma))
+    v = (rng.standard_normal((cfg.K, n), dtype=np.float32) * np.float32(cfg.v_sigma))
+    pbest = x.copy()
+    pbest_loss = np.minimum(losses[0], np.float32(3.0))  # about half of the particles improve
+    gbest = np.empty(n, np.float32)
+    t0 = time.perf_counter()
+    oracle.sync(x, v, pbest, pbest_loss, losses[1], gbest, np.float32(cfg.w[0]),
+                np.float32(cfg.c1), np.float32(cfg.c2), cfg.seed, 0)
+    dt = time.perf_counter() - t0
+    return {"value": cfg.K * n / dt, "unit": "particle-params/s", "cores": 1, "kind": "oracle",
+            "sample": f"one stage, K={cfg.K} x first {n} of {cfg.D} columns of {cfg.name}, "
+                      f"{dt:.1f} s single-threaded"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="resnet50x32")
+    ap.add_argument("--block", type=int, default=0, help="threads per workgroup (0 = default)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also launch one plain device copy of 1 GiB (counter calibration)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); "
+              "--gpus must be 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import paper_2009_03816_amd as pso
+    from paper_2009_03816_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    cfg = wl.CONFIGS[args.workload]
+    K, D = cfg.K, cfg.D
+    dev = torch.device("cuda:0")
+    total = args.warmup + args.steps
+
+    sw = wl.make_swarm(cfg, steps=total)
+    dx = torch.from_numpy(sw.x).to(dev)
+    dv = torch.from_numpy(sw.v).to(dev)
+    dp = dx.clone()
+    dpl = torch.from_numpy(sw.pbest_loss).to(dev)
+    dloss = torch.from_numpy(sw.losses).to(dev)          # [total, K], resident
+    dg = torch.zeros(D, dtype=torch.float32, device=dev)
+    w_tab, c1, c2 = [float(t) for t in sw.w], float(sw.c1), float(sw.c2)
+    del sw
+
+    h = pso.pso_ps_create(K, D)
+    if args.block:
+        pso.pso_ps_set_launch(h, args.block, False)
+    stream = torch.cuda.current_stream()
+
+    def stage(s, ev=None):
+        pso.pso_ps_select(h, dpl, dloss[s], stream)
+        if ev:
+            ev[0].record(stream)
+        pso.pso_ps_update(h, dx, dv, dp, dg, w_tab[s], c1, c2, cfg.seed, s, stream)
+        if ev:
+            ev[1].record(stream)
+
+    for s in range(args.warmup):
+        stage(s)
+    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+              for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        stage(args.warmup + k, events[k])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    kernel_ms = [a.elapsed_time(b) for a, b in events]
+    avg_ms = sum(kernel_ms) / len(kernel_ms)
+    algo_bytes = 4.0 * D * (5 * K + 1)                   # per update launch
+    achieved = algo_bytes / (avg_ms * 1e-3) / 1e9
+    assert bool(torch.isfinite(dx).all()), "state went non-finite"
+
+    if args.copy_probe:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+
+    traffic = MEASURED_TRAFFIC.get((cfg.name, kernel_source_hash()))
+    out = {
+        "metric": "PSO sync particle-params/s", "value": K * D * args.steps / elapsed,
+        "unit": "particle-params/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: K={K} particles x D={D} fp32 parameters, "
+                               f"w={cfg.w[0]}, c1={cfg.c1}, c2={cfg.c2}", "K": K, "D": D},
+        "roofline": {"bound": "hbm", "kernel": "update_vec4_kernel", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": traffic, "algorithmic_bytes_per_launch": algo_bytes,
+                     "kernel_ms_avg": avg_ms, "kernel_ms_min": min(kernel_ms)},
+    }
+    torch.cuda.synchronize()
+    pso.pso_ps_destroy(h)
+    del dx, dv, dp, dg
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

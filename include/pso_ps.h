@@ -1,0 +1,143 @@
+/* pso_ps.h - C ABI of the PSO-PS synchronization step on one AMD GPU.
+ *
+ * One synchronization stage of "PSO-PS: Parameter Synchronization with
+ * Particle Swarm Optimization for Distributed Training of Deep Neural
+ * Networks" (Ye, Han, Sun, Lv): the branch of Algorithm 1 taken every `step`
+ * iterations.  K workers' weight vectors (the particles, Table I) are stacked
+ * as rows of [K, ld] float arrays in device memory, with their training losses
+ * (the fitness, Table I).  A stage
+ *   1. picks the global best g = argmin_i loss_i              (Algorithm 3),
+ *   2. copies gbest = x_g as it is before anybody moves        (Algorithm 3),
+ *   3. for each particle with loss_i < pbest_loss_i sets pbest_i = x_i and
+ *      pbest_loss_i = loss_i                          (Algorithm 1, pBest test),
+ *   4. moves every particle, for every coordinate d,
+ *        v_id <- w v_id + c1 r1 (pbest_id - x_id) + c2 r2 (gbest_d - x_id)
+ *        x_id <- x_id + v_id                                   (Eq. (6), (7)),
+ *      r1, r2 uniform in [0,1) (Table II), independent per (i, d).
+ *
+ * Naming: x = positions = the paper's weights w_i; v = velocities; `w` here is
+ * the inertia weight, the paper's m (Eq. (5) gives its schedule; the caller
+ * evaluates it and passes the value); c1, c2 are the effective acceleration
+ * coefficients, i.e. already divided by the damping lambda of Eq. (6).
+ *
+ * Conventions fixed by this interface (the paper leaves them open):
+ *   - ties in the argmin go to the lowest index; a NaN loss never wins the
+ *     argmin and never improves a personal best; if no loss is below +inf, g = 0;
+ *   - gbest is the best of this stage only (no history across stages);
+ *   - step 4 uses the personal best after step 3;
+ *   - r1, r2 are produced by Philox4x32-10 (Salmon et al., SC'11) with
+ *       counter = (lo32(d >> 1), i, lo32(step), hi32(step)), key = (lo32(seed), hi32(seed)),
+ *       r1 = (word[2(d&1)] >> 8) * 2^-24, r2 = (word[2(d&1)+1] >> 8) * 2^-24,
+ *     where d is the flat coordinate index (for segments: in concatenation
+ *     order).  The result therefore depends only on the arguments, never on
+ *     row stride, segmentation, launch shape or stream;
+ *   - arithmetic is IEEE binary32, round to nearest even, evaluated as
+ *       acc = w*v; acc = fma(c1*r1, pbest - x, acc); acc = fma(c2*r2, gbest - x, acc);
+ *       v = acc; x = x + acc.
+ *
+ * Memory: every array argument is DEVICE memory owned by the caller, float32,
+ * 4-byte aligned (otherwise PSO_PS_EALIGN).  128-bit accesses are used when
+ * the row starts of x, v, pbest are 8-byte aligned and the first flat index
+ * of the block is even; anything else is accepted and takes a slower
+ * element-wise path with identical results.  x, v, pbest, pbest_loss are
+ * updated in place; gbest is written; loss is read.  The arrays must not
+ * overlap each other.  Padding columns D..ld-1 are neither read nor written.
+ *
+ * Execution: the calls enqueue work on `hip_stream` (a hipStream_t passed as
+ * void*, NULL = the default stream) and return without waiting; nothing is
+ * allocated or copied to the host per call.  The handle owns a few bytes of
+ * device scratch (g and the improved mask).  Calls on one handle must be
+ * issued from one host thread at a time and on one stream at a time (work of
+ * two stages on different streams would share the scratch).
+ *
+ * Errors: every function returns PSO_PS_OK (0) or a negative code; nothing
+ * throws or aborts.  On error no work has been enqueued, except that a failed
+ * multi-segment call may have enqueued some segments.
+ */
+#ifndef PSO_PS_H
+#define PSO_PS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PSO_PS_OK       0
+#define PSO_PS_EINVAL  (-1)  /* null pointer, K < 1, D < 1, ld < D, bad segment table, bad handle state */
+#define PSO_PS_EALIGN  (-2)  /* an array is not 4-byte aligned */
+#define PSO_PS_EHIP    (-3)  /* a HIP runtime call failed; see pso_ps_last_hip_error */
+#define PSO_PS_ENOMEM  (-4)  /* host allocation failed */
+
+typedef struct pso_ps_ctx pso_ps_ctx;
+
+/* Create a handle for a swarm of K particles (Table I: population = number of
+ * workers) with D parameters each, on HIP device `device`.
+ *   ld        row stride of the flat [K, ld] arrays in elements, >= D.
+ *   n_seg, seg_sizes (host)  optional ragged structure (Algorithm 2 clones the
+ *             network "including the structure"): n_seg per-layer sizes, each
+ *             >= 0, summing to D.  n_seg = 0 / NULL means one flat block.
+ * The handle is written to *out.  Allocates the device scratch. */
+int pso_ps_create(pso_ps_ctx** out, int K, int64_t D, int64_t ld,
+                  int n_seg, const int64_t* seg_sizes, int device);
+
+/* One whole synchronization stage (steps 1-4 above) on flat arrays.
+ *   x, v, pbest   device [K, ld], in/out      pbest_loss  device [K], in/out
+ *   loss          device [K], in              gbest       device [D], out
+ *   w, c1, c2     inertia (paper's m) and effective accelerations
+ *   seed, step    select the random numbers; the same pair reproduces them
+ * Equivalent to pso_ps_select followed by pso_ps_update. */
+int pso_ps_sync(pso_ps_ctx* h, float* x, float* v, float* pbest,
+                float* pbest_loss, const float* loss, float* gbest,
+                float w, float c1, float c2, uint64_t seed, uint64_t step,
+                void* hip_stream);
+
+/* The same stage on the ragged layout given at create: x_seg, v_seg,
+ * pbest_seg, gbest_seg are HOST arrays of n_seg device pointers; segment s is
+ * a dense [K, seg_sizes[s]] array (gbest_seg[s]: [seg_sizes[s]]).  Pointers of
+ * empty segments are ignored.  Bitwise the same result as the flat call on
+ * the concatenated columns. */
+int pso_ps_sync_segments(pso_ps_ctx* h, float* const* x_seg, float* const* v_seg,
+                         float* const* pbest_seg, float* pbest_loss, const float* loss,
+                         float* const* gbest_seg, float w, float c1, float c2,
+                         uint64_t seed, uint64_t step, void* hip_stream);
+
+/* Steps 1 and 3 (selection part): g = argmin loss (Algorithm 3), improved_i =
+ * loss_i < pbest_loss_i and pbest_loss_i = min(pbest_loss_i, loss_i)
+ * (Algorithm 1).  g and the improved mask stay in the handle's scratch. */
+int pso_ps_select(pso_ps_ctx* h, float* pbest_loss, const float* loss, void* hip_stream);
+
+/* Steps 2, 3 (copy part) and 4 for the selection left by the last
+ * pso_ps_select on this handle (same stream): gbest = x_g, pbest_i = x_i for
+ * improved particles, then Eq. (6), (7) over all K*D elements. */
+int pso_ps_update(pso_ps_ctx* h, float* x, float* v, float* pbest, float* gbest,
+                  float w, float c1, float c2, uint64_t seed, uint64_t step,
+                  void* hip_stream);
+
+/* Read back the last selection: waits for the stream of the last call on this
+ * handle, then writes g to *g_out and the improved flags, bit i of word i/64,
+ * to improved_mask_out[0..mask_words-1] (host; mask_words >= (K+63)/64).
+ * Either output may be NULL.  For tests and logging, not for the hot path. */
+int pso_ps_last_selection(pso_ps_ctx* h, int* g_out, uint64_t* improved_mask_out,
+                          int mask_words);
+
+/* Launch shape of the update kernel: threads per workgroup (64, 128, 256, 512
+ * or 1024; 0 = library default) and whether to force the element-wise path
+ * (force_generic != 0) even where 128-bit accesses are possible.  Results are
+ * bitwise independent of both; the call exists for measurement and tests. */
+int pso_ps_set_launch(pso_ps_ctx* h, int block_threads, int force_generic);
+
+/* hipError_t (as int) of the last failed HIP call on this handle, 0 if none. */
+int pso_ps_last_hip_error(const pso_ps_ctx* h);
+
+/* Free the scratch and the handle.  The caller must have synchronized the
+ * streams it used with this handle.  NULL is accepted. */
+int pso_ps_destroy(pso_ps_ctx* h);
+
+/* Static, human-readable text for a status code. */
+const char* pso_ps_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PSO_PS_H */

@@ -1,0 +1,156 @@
+"""ctypes binding of libpso_ps.so: the functions of include/pso_ps.h under the
+same names.  Argument marshalling only; every step of the synchronization
+stage runs in the library's HIP kernels.  Array arguments are torch tensors on
+the GPU (or anything with ``data_ptr()``) or raw device addresses as ints.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+from . import build as _build
+
+PSO_PS_OK = 0
+PSO_PS_EINVAL = -1
+PSO_PS_EALIGN = -2
+PSO_PS_EHIP = -3
+PSO_PS_ENOMEM = -4
+
+_f32p = ctypes.c_void_p   # device addresses travel as plain pointers
+_lib = None
+
+
+class PsoPsError(RuntimeError):
+    def __init__(self, code: int, where: str, hip_error: int = 0):
+        self.code, self.hip_error = code, hip_error
+        extra = f" (hipError {hip_error})" if hip_error else ""
+        super().__init__(f"{where}: {pso_ps_strerror(code)} [{code}]{extra}")
+
+
+def library_path() -> str:
+    return _build.LIBRARY
+
+
+def load():
+    """Load the built library; build it first if it has never been built.
+    Raises if it can be neither found nor built: there is no fallback path."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIBRARY):
+        _build.build_library()
+    # torch first: the library then binds to the HIP runtime torch has already
+    # loaded, so that torch's streams and allocations are valid in its calls.
+    import torch  # noqa: F401
+    lib = ctypes.CDLL(_build.LIBRARY)
+    P, I, I64, U64, F = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_uint64, ctypes.c_float
+    PP = ctypes.POINTER(ctypes.c_void_p)
+    lib.pso_ps_create.argtypes = [PP, I, I64, I64, I, ctypes.POINTER(I64), I]
+    lib.pso_ps_sync.argtypes = [P, _f32p, _f32p, _f32p, _f32p, _f32p, _f32p, F, F, F, U64, U64, P]
+    lib.pso_ps_sync_segments.argtypes = [P, PP, PP, PP, _f32p, _f32p, PP, F, F, F, U64, U64, P]
+    lib.pso_ps_select.argtypes = [P, _f32p, _f32p, P]
+    lib.pso_ps_update.argtypes = [P, _f32p, _f32p, _f32p, _f32p, F, F, F, U64, U64, P]
+    lib.pso_ps_last_selection.argtypes = [P, ctypes.POINTER(I), ctypes.POINTER(U64), I]
+    lib.pso_ps_set_launch.argtypes = [P, I, I]
+    lib.pso_ps_last_hip_error.argtypes = [P]
+    lib.pso_ps_destroy.argtypes = [P]
+    lib.pso_ps_strerror.argtypes = [I]
+    for name in ("pso_ps_create", "pso_ps_sync", "pso_ps_sync_segments", "pso_ps_select",
+                 "pso_ps_update", "pso_ps_last_selection", "pso_ps_set_launch",
+                 "pso_ps_last_hip_error", "pso_ps_destroy"):
+        getattr(lib, name).restype = I
+    lib.pso_ps_strerror.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def _addr(a) -> Optional[int]:
+    if a is None:
+        return None
+    if isinstance(a, int):
+        return a
+    return int(a.data_ptr())
+
+
+def _stream(stream) -> Optional[int]:
+    """A torch stream, a raw hipStream_t as int, or None for torch's current stream."""
+    if stream is None:
+        import torch
+        return int(torch.cuda.current_stream().cuda_stream) or None
+    if isinstance(stream, int):
+        return stream or None
+    return int(stream.cuda_stream) or None
+
+
+def _table(ptrs: Sequence):
+    return (ctypes.c_void_p * len(ptrs))(*[_addr(p) for p in ptrs])
+
+
+def _check(rc: int, where: str, h=None):
+    if rc != PSO_PS_OK:
+        raise PsoPsError(rc, where, pso_ps_last_hip_error(h) if h else 0)
+
+
+def pso_ps_strerror(code: int) -> str:
+    return load().pso_ps_strerror(code).decode()
+
+
+def pso_ps_create(K: int, D: int, ld: Optional[int] = None, seg_sizes: Optional[Sequence[int]] = None,
+                  device: int = 0) -> int:
+    """Returns the handle (an opaque integer)."""
+    lib = load()
+    h = ctypes.c_void_p()
+    n_seg = 0 if seg_sizes is None else len(seg_sizes)
+    sizes = (ctypes.c_int64 * n_seg)(*seg_sizes) if n_seg else None
+    rc = lib.pso_ps_create(ctypes.byref(h), K, D, D if ld is None else ld, n_seg, sizes, device)
+    _check(rc, "pso_ps_create")
+    return h.value
+
+
+def pso_ps_sync(h: int, x, v, pbest, pbest_loss, loss, gbest, w: float, c1: float, c2: float,
+                seed: int, step: int, stream=None) -> None:
+    rc = load().pso_ps_sync(h, _addr(x), _addr(v), _addr(pbest), _addr(pbest_loss), _addr(loss),
+                            _addr(gbest), w, c1, c2, seed, step, _stream(stream))
+    _check(rc, "pso_ps_sync", h)
+
+
+def pso_ps_sync_segments(h: int, x_seg, v_seg, pbest_seg, pbest_loss, loss, gbest_seg,
+                         w: float, c1: float, c2: float, seed: int, step: int, stream=None) -> None:
+    rc = load().pso_ps_sync_segments(h, _table(x_seg), _table(v_seg), _table(pbest_seg),
+                                     _addr(pbest_loss), _addr(loss), _table(gbest_seg),
+                                     w, c1, c2, seed, step, _stream(stream))
+    _check(rc, "pso_ps_sync_segments", h)
+
+
+def pso_ps_select(h: int, pbest_loss, loss, stream=None) -> None:
+    _check(load().pso_ps_select(h, _addr(pbest_loss), _addr(loss), _stream(stream)),
+           "pso_ps_select", h)
+
+
+def pso_ps_update(h: int, x, v, pbest, gbest, w: float, c1: float, c2: float, seed: int, step: int,
+                  stream=None) -> None:
+    rc = load().pso_ps_update(h, _addr(x), _addr(v), _addr(pbest), _addr(gbest), w, c1, c2,
+                              seed, step, _stream(stream))
+    _check(rc, "pso_ps_update", h)
+
+
+def pso_ps_last_selection(h: int, K: int):
+    """(g, improved) with improved a list of K bools.  Waits for the stream."""
+    words = (K + 63) // 64
+    g = ctypes.c_int(-1)
+    mask = (ctypes.c_uint64 * words)()
+    _check(load().pso_ps_last_selection(h, ctypes.byref(g), mask, words), "pso_ps_last_selection", h)
+    return int(g.value), [bool((mask[i >> 6] >> (i & 63)) & 1) for i in range(K)]
+
+
+def pso_ps_set_launch(h: int, block_threads: int = 0, force_generic: bool = False) -> None:
+    _check(load().pso_ps_set_launch(h, block_threads, int(force_generic)), "pso_ps_set_launch", h)
+
+
+def pso_ps_last_hip_error(h: int) -> int:
+    return int(load().pso_ps_last_hip_error(h))
+
+
+def pso_ps_destroy(h: Optional[int]) -> None:
+    _check(load().pso_ps_destroy(h), "pso_ps_destroy")

@@ -1,0 +1,237 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU
+oracle on the same seeded inputs.  Bar: identical g, improved flags,
+pbest_loss, pbest and gbest; x and v within 1e-6 relative (and, by design,
+identical in bits)."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2009_03816_amd as pso
+from paper_2009_03816_amd import workloads as wl
+
+import gpu_harness as gh
+
+pytestmark = pytest.mark.gpu
+F32 = np.float32
+
+
+def run_trajectory(oracle, sw, steps=None, **kw):
+    pair = gh.Pair(sw, **kw)
+    try:
+        for s in range(sw.cfg.steps if steps is None else steps):
+            g, improved = pair.step(oracle, s)
+            pair.check(g, improved, f"{sw.cfg.name} step {s}")
+    finally:
+        pair.close()
+
+
+@pytest.mark.parametrize("name", ["mlp", "lenet5", "resnet20"])
+def test_config_trajectory(oracle, name):
+    print(f"[case] config {name}, dense rows", flush=True)
+    run_trajectory(oracle, wl.make_swarm(wl.CONFIGS[name]))
+
+
+@pytest.mark.parametrize("name", ["mlp", "resnet20"])
+def test_config_trajectory_padded_rows(oracle, name):
+    cfg = wl.CONFIGS[name]
+    ld = (cfg.D + 3) // 4 * 4 + 4
+    print(f"[case] config {name}, ld={ld}", flush=True)
+    run_trajectory(oracle, wl.make_swarm(cfg, ld=ld), steps=min(cfg.steps, 6))
+
+
+def test_lenet5_segments_match_flat_and_oracle(oracle):
+    """The ragged per-layer layout gives the bits of the flat layout."""
+    cfg = wl.CONFIGS["lenet5"]
+    print(f"[case] config lenet5, {len(cfg.segments)} segments", flush=True)
+    sw = wl.make_swarm(cfg)
+    sizes = list(cfg.segments)
+    hx, hv, hp, hpl = sw.x.copy(), sw.v.copy(), sw.pbest.copy(), sw.pbest_loss.copy()
+    hg = np.zeros(cfg.D, F32)
+    dx, dv, dp = ([gh.to_dev(a) for a in wl.segment_views(t, sizes)] for t in (sw.x, sw.v, sw.pbest))
+    dg = [torch.zeros(n, dtype=torch.float32, device=gh.dev()) for n in sizes]
+    dpl = gh.to_dev(sw.pbest_loss)
+    h = pso.pso_ps_create(cfg.K, cfg.D, cfg.D, seg_sizes=sizes)
+    try:
+        for s in range(cfg.steps):
+            w, c1, c2 = float(sw.w[s]), float(sw.c1), float(sw.c2)
+            pso.pso_ps_sync_segments(h, dx, dv, dp, dpl, gh.to_dev(sw.losses[s]), dg,
+                                     w, c1, c2, cfg.seed, s)
+            g, improved = oracle.sync(hx, hv, hp, hpl, sw.losses[s], hg, F32(w), F32(c1), F32(c2),
+                                      cfg.seed, s)
+            gg, gi = pso.pso_ps_last_selection(h, cfg.K)
+            assert gg == g and gi == [bool(t) for t in improved]
+            cat = lambda parts: np.concatenate([t.cpu().numpy() for t in parts], axis=-1)
+            gh.assert_bits_equal(cat(dp), hp, f"segments step {s}: pbest")
+            gh.assert_bits_equal(cat(dg), hg, f"segments step {s}: gbest")
+            gh.assert_close(cat(dx), hx, f"segments step {s}: x")
+            gh.assert_close(cat(dv), hv, f"segments step {s}: v")
+            gh.assert_bits_equal(dpl.cpu().numpy(), hpl, f"segments step {s}: pbest_loss")
+    finally:
+        torch.cuda.synchronize()
+        pso.pso_ps_destroy(h)
+
+
+def test_odd_and_empty_segments(oracle):
+    """Segment sizes that are odd (a Philox pair straddles two segments),
+    one, and zero."""
+    sizes = [5, 0, 1, 1024, 3, 4097, 2, 7]
+    K, D = 5, sum(sizes)
+    print(f"[case] odd segments K={K} sizes={sizes}", flush=True)
+    sw = wl.small_swarm(K, D, seed=21, steps=3)
+    hx, hv, hp, hpl = sw.x.copy(), sw.v.copy(), sw.pbest.copy(), sw.pbest_loss.copy()
+    hg = np.zeros(D, F32)
+    dx, dv, dp = ([gh.to_dev(a) for a in wl.segment_views(t, sizes)] for t in (sw.x, sw.v, sw.pbest))
+    dg = [torch.zeros(max(n, 1), dtype=torch.float32, device=gh.dev())[:n] for n in sizes]
+    dpl = gh.to_dev(sw.pbest_loss)
+    h = pso.pso_ps_create(K, D, D, seg_sizes=sizes)
+    try:
+        for s in range(3):
+            pso.pso_ps_sync_segments(h, dx, dv, dp, dpl, gh.to_dev(sw.losses[s]), dg,
+                                     0.7, 1.5, 1.5, 21, s)
+            oracle.sync(hx, hv, hp, hpl, sw.losses[s], hg, F32(0.7), F32(1.5), F32(1.5), 21, s)
+            cat = lambda parts: np.concatenate([t.cpu().numpy() for t in parts], axis=-1)
+            gh.assert_bits_equal(cat(dp), hp, f"odd segments step {s}: pbest")
+            gh.assert_bits_equal(cat(dg), hg, f"odd segments step {s}: gbest")
+            gh.assert_close(cat(dx), hx, f"odd segments step {s}: x")
+            gh.assert_close(cat(dv), hv, f"odd segments step {s}: v")
+    finally:
+        torch.cuda.synchronize()
+        pso.pso_ps_destroy(h)
+
+
+@pytest.mark.parametrize("K,D,ld,offset", [
+    (1, 1, 1, 0), (1, 7, 7, 0), (2, 2, 2, 0), (3, 3, 4, 0), (2, 5, 5, 0),       # tiny, odd
+    (4, 1026, 1026, 0),                      # D = 2 mod 4: every other row is 8-byte aligned only
+    (4, 1026, 1028, 0),                      # padded to 16-byte rows
+    (3, 4099, 4099, 0),                      # odd D and stride: element-wise path
+    (6, 2048 + 1, 2050, 0),                  # odd D, even stride: ragged last column
+    (6, 2048 + 3, 2052, 0),                  # three ragged columns
+    (5, 3000, 3000, 1),                      # buffers 4-byte aligned only
+    (5, 3000, 3000, 2),                      # buffers 8-byte aligned only
+    (33, 1500, 1500, 0), (64, 260, 260, 0), (65, 260, 260, 0), (130, 132, 132, 0),   # K beyond a wave
+    (7, 70_000, 70_000, 0),                  # several workgroups and a ragged last one
+])
+def test_shapes_and_alignments(oracle, K, D, ld, offset):
+    print(f"[case] K={K} D={D} ld={ld} offset={offset}", flush=True)
+    sw = wl.small_swarm(K, D, seed=100 + K + D, ld=ld, steps=3)
+    sw.x[:, D:] = 7.0; sw.v[:, D:] = 7.0; sw.pbest[:, D:] = 7.0     # padding must stay untouched
+    run_trajectory(oracle, sw, steps=3, offset=offset)
+
+
+@pytest.mark.parametrize("block,generic", [(64, False), (128, False), (512, False), (1024, False),
+                                           (64, True), (256, True)])
+def test_launch_shape_does_not_change_bits(oracle, block, generic):
+    print(f"[case] block={block} generic={generic}", flush=True)
+    sw = wl.small_swarm(9, 10_242, seed=5, steps=2)
+    run_trajectory(oracle, sw, steps=2, block_threads=block, force_generic=generic)
+
+
+def test_ties_nan_and_inf_losses(oracle):
+    K, D = 8, 5000
+    print(f"[case] ties / NaN / inf losses K={K} D={D}", flush=True)
+    sw = wl.small_swarm(K, D, seed=77, steps=1)
+    nan, inf = np.nan, np.inf
+    tables = [
+        [1.0, 0.5, 0.5, 2.0, 0.5, 3.0, 4.0, 5.0],          # three-way tie for the minimum
+        [nan, nan, 0.7, nan, 0.7, nan, nan, nan],          # NaN never wins
+        [1.0, 0.5, 0.5, 2.0, 0.4, 0.7, 4.0, nan],          # equal to own pbest_loss: no improvement
+        [nan] * 8, [inf] * 8, [inf, -inf, 1.0, -inf, nan, 0.0, -0.0, 2.0],
+    ]
+    pair = gh.Pair(sw)
+    try:
+        for s, row in enumerate(tables):
+            g, improved = pair.step(oracle, s, loss=np.array(row, F32))
+            pair.check(g, improved, f"loss table {s}")
+    finally:
+        pair.close()
+
+
+def test_deterministic_and_resumable(oracle):
+    """Same (seed, step) gives the same bits; five stages, a new handle and
+    five more equal ten stages in one go."""
+    print("[case] determinism / resume", flush=True)
+    cfg = wl.CONFIGS["mlp"]
+    sw = wl.make_swarm(cfg, steps=10)
+
+    def advance(state, h, lo, hi):
+        for s in range(lo, hi):
+            pso.pso_ps_sync(h, state[0], state[1], state[2], state[3], gh.to_dev(sw.losses[s]),
+                            state[4], 0.7, 1.5, 1.5, 0, s)
+
+    def fresh():
+        return [gh.to_dev(a) for a in (sw.x, sw.v, sw.pbest, sw.pbest_loss, np.zeros(cfg.D, F32))]
+
+    a, b = fresh(), fresh()
+    ha = pso.pso_ps_create(cfg.K, cfg.D); advance(a, ha, 0, 10)
+    hb = pso.pso_ps_create(cfg.K, cfg.D); advance(b, hb, 0, 5)
+    torch.cuda.synchronize(); pso.pso_ps_destroy(hb)
+    hb = pso.pso_ps_create(cfg.K, cfg.D); advance(b, hb, 5, 10)
+    torch.cuda.synchronize()
+    for ta, tb in zip(a, b):
+        assert torch.equal(ta.view(torch.int32), tb.view(torch.int32))
+    pso.pso_ps_destroy(ha); pso.pso_ps_destroy(hb)
+
+
+def test_select_then_update_equals_sync(oracle):
+    print("[case] select + update == sync", flush=True)
+    sw = wl.small_swarm(6, 9000, seed=3, steps=1)
+    one = [gh.to_dev(a) for a in (sw.x, sw.v, sw.pbest, sw.pbest_loss, np.zeros(9000, F32))]
+    two = [gh.to_dev(a) for a in (sw.x, sw.v, sw.pbest, sw.pbest_loss, np.zeros(9000, F32))]
+    loss = gh.to_dev(sw.losses[0])
+    h = pso.pso_ps_create(6, 9000)
+    pso.pso_ps_sync(h, one[0], one[1], one[2], one[3], loss, one[4], 0.7, 1.5, 1.5, 9, 4)
+    pso.pso_ps_select(h, two[3], loss)
+    pso.pso_ps_update(h, two[0], two[1], two[2], two[4], 0.7, 1.5, 1.5, 9, 4)
+    torch.cuda.synchronize()
+    for ta, tb in zip(one, two):
+        assert torch.equal(ta.view(torch.int32), tb.view(torch.int32))
+    pso.pso_ps_destroy(h)
+
+
+def test_runs_on_a_side_stream(oracle):
+    print("[case] non-default stream", flush=True)
+    sw = wl.small_swarm(4, 4096, seed=12, steps=1)
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        run_trajectory(oracle, sw, steps=1)
+
+
+def test_error_codes():
+    print("[case] error codes", flush=True)
+    with pytest.raises(pso.PsoPsError) as e:
+        pso.pso_ps_create(0, 10)
+    assert e.value.code == pso.PSO_PS_EINVAL
+    for bad in [dict(K=2, D=0), dict(K=2, D=10, ld=9), dict(K=2, D=10, seg_sizes=[4, 5]),
+                dict(K=2, D=10, seg_sizes=[11, -1])]:
+        with pytest.raises(pso.PsoPsError) as e:
+            pso.pso_ps_create(**bad)
+        assert e.value.code == pso.PSO_PS_EINVAL, bad
+    h = pso.pso_ps_create(2, 10)
+    t = torch.zeros(1024, dtype=torch.float32, device=gh.dev())
+    ok = t.data_ptr()
+    args = lambda **kw: {**dict(x=ok, v=ok + 256, pbest=ok + 512, pbest_loss=ok + 768,
+                                 loss=ok + 800, gbest=ok + 900), **kw}
+    def call(**kw):
+        a = args(**kw)
+        pso.pso_ps_sync(h, a["x"], a["v"], a["pbest"], a["pbest_loss"], a["loss"], a["gbest"],
+                        0.5, 1.0, 1.0, 0, 0)
+    for name in ("x", "v", "pbest", "pbest_loss", "loss", "gbest"):
+        with pytest.raises(pso.PsoPsError) as e:
+            call(**{name: None})
+        assert e.value.code == pso.PSO_PS_EINVAL, name
+        with pytest.raises(pso.PsoPsError) as e:
+            call(**{name: ok + 2})
+        assert e.value.code == pso.PSO_PS_EALIGN, name
+    with pytest.raises(pso.PsoPsError) as e:      # update before any select
+        pso.pso_ps_update(h, ok, ok + 256, ok + 512, ok + 900, 0.5, 1.0, 1.0, 0, 0)
+    assert e.value.code == pso.PSO_PS_EINVAL
+    with pytest.raises(pso.PsoPsError) as e:      # flat handle has no segment table
+        pso.pso_ps_sync_segments(h, [ok], [ok], [ok], ok, ok, [ok], 0.5, 1.0, 1.0, 0, 0)
+    assert e.value.code == pso.PSO_PS_EINVAL
+    with pytest.raises(pso.PsoPsError):
+        pso.pso_ps_set_launch(h, 100)
+    torch.cuda.synchronize()
+    assert not t.any()                           # nothing was enqueued by the failed calls
+    pso.pso_ps_destroy(h)
+    pso.pso_ps_destroy(None)
