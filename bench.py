@@ -71,6 +71,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="resnet50x32")
     ap.add_argument("--block", type=int, default=0, help="threads per workgroup (0 = default)")
+    ap.add_argument("--super-tiles", type=int, default=0)
+    ap.add_argument("--chunk-tiles", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch one plain device copy of 1 GiB (counter calibration)")
@@ -104,12 +106,12 @@ def main() -> int:
     del sw
 
     h = pso.pso_ps_create(K, D)
-    if args.block:
-        pso.pso_ps_set_launch(h, args.block, False)
+    if args.block or args.super_tiles or args.chunk_tiles:
+        pso.pso_ps_set_launch(h, args.block, args.super_tiles, args.chunk_tiles, False)
     stream = torch.cuda.current_stream()
 
     def stage(s, ev=None):
-        pso.pso_ps_select(h, dpl, dloss[s], stream)
+        pso.pso_ps_select(h, dx, dpl, dloss[s], dg, stream)
         if ev:
             ev[0].record(stream)
         pso.pso_ps_update(h, dx, dv, dp, dg, w_tab[s], c1, c2, cfg.seed, s, stream)
@@ -147,7 +149,7 @@ def main() -> int:
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: K={K} particles x D={D} fp32 parameters, "
                                f"w={cfg.w[0]}, c1={cfg.c1}, c2={cfg.c2}", "K": K, "D": D},
-        "roofline": {"bound": "hbm", "kernel": "update_vec4_kernel", "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": "update_kernel", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic, "algorithmic_bytes_per_launch": algo_bytes,
                      "kernel_ms_avg": avg_ms, "kernel_ms_min": min(kernel_ms)},

@@ -37,8 +37,9 @@
  *
  * Memory: every array argument is DEVICE memory owned by the caller, float32,
  * 4-byte aligned (otherwise PSO_PS_EALIGN).  128-bit accesses are used when
- * the row starts of x, v, pbest are 8-byte aligned and the first flat index
- * of the block is even; anything else is accepted and takes a slower
+ * x, v and pbest are congruent modulo 16 bytes, the row stride is even (or
+ * K = 1) and x is 8-byte aligned (for a segment: its address/4 plus its first
+ * flat index is even); anything else is accepted and takes a slower
  * element-wise path with identical results.  x, v, pbest, pbest_loss are
  * updated in place; gbest is written; loss is read.  The arrays must not
  * overlap each other.  Padding columns D..ld-1 are neither read nor written.
@@ -102,15 +103,19 @@ int pso_ps_sync_segments(pso_ps_ctx* h, float* const* x_seg, float* const* v_seg
                          float* const* gbest_seg, float w, float c1, float c2,
                          uint64_t seed, uint64_t step, void* hip_stream);
 
-/* Steps 1 and 3 (selection part): g = argmin loss (Algorithm 3), improved_i =
- * loss_i < pbest_loss_i and pbest_loss_i = min(pbest_loss_i, loss_i)
- * (Algorithm 1).  g and the improved mask stay in the handle's scratch. */
-int pso_ps_select(pso_ps_ctx* h, float* pbest_loss, const float* loss, void* hip_stream);
+/* Global search and personal-best test (steps 1, 2 and the test of step 3):
+ * g = argmin loss and gbest = x_g, i.e. what Algorithm 3 returns, plus
+ * improved_i = loss_i < pbest_loss_i and pbest_loss_i = min(pbest_loss_i,
+ * loss_i) (Algorithm 1).  g and the improved mask stay in the handle's scratch.
+ *   x  device [K, ld], read        gbest  device [D], written */
+int pso_ps_select(pso_ps_ctx* h, const float* x, float* pbest_loss, const float* loss,
+                  float* gbest, void* hip_stream);
 
-/* Steps 2, 3 (copy part) and 4 for the selection left by the last
- * pso_ps_select on this handle (same stream): gbest = x_g, pbest_i = x_i for
- * improved particles, then Eq. (6), (7) over all K*D elements. */
-int pso_ps_update(pso_ps_ctx* h, float* x, float* v, float* pbest, float* gbest,
+/* The per-particle part (copy of step 3 and step 4) for the selection left by
+ * the last pso_ps_select on this handle (same stream): pbest_i = x_i for
+ * improved particles, then Eq. (6), (7) over all K*D elements.  gbest (device
+ * [D], read) is the array pso_ps_select wrote. */
+int pso_ps_update(pso_ps_ctx* h, float* x, float* v, float* pbest, const float* gbest,
                   float w, float c1, float c2, uint64_t seed, uint64_t step,
                   void* hip_stream);
 
@@ -121,11 +126,17 @@ int pso_ps_update(pso_ps_ctx* h, float* x, float* v, float* pbest, float* gbest,
 int pso_ps_last_selection(pso_ps_ctx* h, int* g_out, uint64_t* improved_mask_out,
                           int mask_words);
 
-/* Launch shape of the update kernel: threads per workgroup (64, 128, 256, 512
- * or 1024; 0 = library default) and whether to force the element-wise path
- * (force_generic != 0) even where 128-bit accesses are possible.  Results are
- * bitwise independent of both; the call exists for measurement and tests. */
-int pso_ps_set_launch(pso_ps_ctx* h, int block_threads, int force_generic);
+/* Launch shape of the update kernel, for measurement and tests; results are
+ * bitwise independent of all of it.  0 selects the library default.
+ *   block_threads  threads per workgroup: 64, 128, 256, 512 or 1024; a tile is
+ *                  block_threads*4 consecutive floats of one row
+ *   super_tiles    tiles (power of two) that one XCD walks for every row before
+ *                  it moves on; bounds the gbest footprint in that XCD's L2
+ *   chunk_tiles    consecutive tiles (power of two <= super_tiles) handed to
+ *                  one XCD at a time
+ *   force_generic  != 0: element-wise path even where 128-bit accesses are possible */
+int pso_ps_set_launch(pso_ps_ctx* h, int block_threads, int super_tiles, int chunk_tiles,
+                      int force_generic);
 
 /* hipError_t (as int) of the last failed HIP call on this handle, 0 if none. */
 int pso_ps_last_hip_error(const pso_ps_ctx* h);

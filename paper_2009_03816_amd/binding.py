@@ -49,10 +49,10 @@ def load():
     lib.pso_ps_create.argtypes = [PP, I, I64, I64, I, ctypes.POINTER(I64), I]
     lib.pso_ps_sync.argtypes = [P, _f32p, _f32p, _f32p, _f32p, _f32p, _f32p, F, F, F, U64, U64, P]
     lib.pso_ps_sync_segments.argtypes = [P, PP, PP, PP, _f32p, _f32p, PP, F, F, F, U64, U64, P]
-    lib.pso_ps_select.argtypes = [P, _f32p, _f32p, P]
+    lib.pso_ps_select.argtypes = [P, _f32p, _f32p, _f32p, _f32p, P]
     lib.pso_ps_update.argtypes = [P, _f32p, _f32p, _f32p, _f32p, F, F, F, U64, U64, P]
     lib.pso_ps_last_selection.argtypes = [P, ctypes.POINTER(I), ctypes.POINTER(U64), I]
-    lib.pso_ps_set_launch.argtypes = [P, I, I]
+    lib.pso_ps_set_launch.argtypes = [P, I, I, I, I]
     lib.pso_ps_last_hip_error.argtypes = [P]
     lib.pso_ps_destroy.argtypes = [P]
     lib.pso_ps_strerror.argtypes = [I]
@@ -123,9 +123,9 @@ def pso_ps_sync_segments(h: int, x_seg, v_seg, pbest_seg, pbest_loss, loss, gbes
     _check(rc, "pso_ps_sync_segments", h)
 
 
-def pso_ps_select(h: int, pbest_loss, loss, stream=None) -> None:
-    _check(load().pso_ps_select(h, _addr(pbest_loss), _addr(loss), _stream(stream)),
-           "pso_ps_select", h)
+def pso_ps_select(h: int, x, pbest_loss, loss, gbest, stream=None) -> None:
+    _check(load().pso_ps_select(h, _addr(x), _addr(pbest_loss), _addr(loss), _addr(gbest),
+                                _stream(stream)), "pso_ps_select", h)
 
 
 def pso_ps_update(h: int, x, v, pbest, gbest, w: float, c1: float, c2: float, seed: int, step: int,
@@ -144,8 +144,10 @@ def pso_ps_last_selection(h: int, K: int):
     return int(g.value), [bool((mask[i >> 6] >> (i & 63)) & 1) for i in range(K)]
 
 
-def pso_ps_set_launch(h: int, block_threads: int = 0, force_generic: bool = False) -> None:
-    _check(load().pso_ps_set_launch(h, block_threads, int(force_generic)), "pso_ps_set_launch", h)
+def pso_ps_set_launch(h: int, block_threads: int = 0, super_tiles: int = 0, chunk_tiles: int = 0,
+                      force_generic: bool = False) -> None:
+    _check(load().pso_ps_set_launch(h, block_threads, super_tiles, chunk_tiles, int(force_generic)),
+           "pso_ps_set_launch", h)
 
 
 def pso_ps_last_hip_error(h: int) -> int:

@@ -53,7 +53,8 @@ class Pair:
     """One swarm held twice: on the device for the library, on the host for
     the oracle."""
 
-    def __init__(self, sw, offset: int = 0, block_threads: int = 0, force_generic: bool = False):
+    def __init__(self, sw, offset: int = 0, block_threads: int = 0, super_tiles: int = 0,
+                 chunk_tiles: int = 0, force_generic: bool = False):
         self.sw, self.K, self.D, self.ld = sw, sw.cfg.K, sw.cfg.D, sw.ld
         self.hx, self.hv, self.hp = sw.x.copy(), sw.v.copy(), sw.pbest.copy()
         self.hpl = sw.pbest_loss.copy()
@@ -62,8 +63,8 @@ class Pair:
         self.dpl = to_dev(sw.pbest_loss)
         self.dg = torch.zeros(self.D + offset, dtype=torch.float32, device=dev())[offset:]
         self.h = pso.pso_ps_create(self.K, self.D, self.ld)
-        if block_threads or force_generic:
-            pso.pso_ps_set_launch(self.h, block_threads, force_generic)
+        if block_threads or super_tiles or chunk_tiles or force_generic:
+            pso.pso_ps_set_launch(self.h, block_threads, super_tiles, chunk_tiles, force_generic)
 
     def close(self):
         torch.cuda.synchronize()

@@ -118,12 +118,16 @@ def test_shapes_and_alignments(oracle, K, D, ld, offset):
     run_trajectory(oracle, sw, steps=3, offset=offset)
 
 
-@pytest.mark.parametrize("block,generic", [(64, False), (128, False), (512, False), (1024, False),
-                                           (64, True), (256, True)])
-def test_launch_shape_does_not_change_bits(oracle, block, generic):
-    print(f"[case] block={block} generic={generic}", flush=True)
-    sw = wl.small_swarm(9, 10_242, seed=5, steps=2)
-    run_trajectory(oracle, sw, steps=2, block_threads=block, force_generic=generic)
+@pytest.mark.parametrize("block,sup,chunk,generic", [
+    (64, 0, 0, False), (128, 0, 0, False), (512, 0, 0, False), (1024, 0, 0, False),
+    (64, 0, 0, True), (256, 0, 0, True),
+    (64, 2, 1, False), (64, 4, 4, False), (64, 8, 2, False), (128, 16, 16, False),   # XCD-aware orders
+    (256, 1, 1, False), (64, 32, 8, True)])
+def test_launch_shape_does_not_change_bits(oracle, block, sup, chunk, generic):
+    print(f"[case] block={block} super={sup} chunk={chunk} generic={generic}", flush=True)
+    sw = wl.small_swarm(9, 70_002, seed=5, steps=2)
+    run_trajectory(oracle, sw, steps=2, block_threads=block, super_tiles=sup, chunk_tiles=chunk,
+                   force_generic=generic)
 
 
 def test_ties_nan_and_inf_losses(oracle):
@@ -180,7 +184,7 @@ def test_select_then_update_equals_sync(oracle):
     loss = gh.to_dev(sw.losses[0])
     h = pso.pso_ps_create(6, 9000)
     pso.pso_ps_sync(h, one[0], one[1], one[2], one[3], loss, one[4], 0.7, 1.5, 1.5, 9, 4)
-    pso.pso_ps_select(h, two[3], loss)
+    pso.pso_ps_select(h, two[0], two[3], loss, two[4])
     pso.pso_ps_update(h, two[0], two[1], two[2], two[4], 0.7, 1.5, 1.5, 9, 4)
     torch.cuda.synchronize()
     for ta, tb in zip(one, two):
@@ -229,8 +233,9 @@ def test_error_codes():
     with pytest.raises(pso.PsoPsError) as e:      # flat handle has no segment table
         pso.pso_ps_sync_segments(h, [ok], [ok], [ok], ok, ok, [ok], 0.5, 1.0, 1.0, 0, 0)
     assert e.value.code == pso.PSO_PS_EINVAL
-    with pytest.raises(pso.PsoPsError):
-        pso.pso_ps_set_launch(h, 100)
+    for bad in [(100, 0, 0), (256, 3, 0), (256, 0, 6)]:
+        with pytest.raises(pso.PsoPsError):
+            pso.pso_ps_set_launch(h, *bad)
     torch.cuda.synchronize()
     assert not t.any()                           # nothing was enqueued by the failed calls
     pso.pso_ps_destroy(h)
