@@ -28,7 +28,10 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 # WRITE_SIZE, each scaled by what the counter reads for a plain copy of known
 # size), keyed by workload and by the hash of the kernel source they were taken
 # with: a changed kernel reports null until the counters are taken again.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    # profiles/update_kernel_resnet50x32_hbm_traffic.md: mean of three timed launches
+    ("resnet50x32", "8e14e7c189ba7b32"): 16464141000.0,
+}
 
 
 def kernel_source_hash() -> str:
