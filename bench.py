@@ -40,7 +40,7 @@ def kernel_source_hash() -> str:
         return hashlib.sha256(f.read()).hexdigest()[:16]
 
 
-def cpu_baseline(cfg, seconds_target: float = 12.0):
+def cpu_baseline(cfg, seconds_target: float = 15.0):
     """The oracle as it stands, single-threaded, on the first columns of the
     same swarm: one stage, sized for roughly `seconds_target` of CPU work."""
     import numpy as np
@@ -48,8 +48,16 @@ def cpu_baseline(cfg, seconds_target: float = 12.0):
     from paper_2009_03816_amd import workloads as wl
 
     oracle.build()
-    rate_guess = 25e6                                   # elements/s, order of magnitude only
-    n = int(min(cfg.D, max(1024, seconds_target * rate_guess / cfg.K)))
+    # size the sample from a short calibration pass of the same routine
+    nc = 1 << 15
+    cal = [np.zeros((cfg.K, nc), np.float32) for _ in range(3)]
+    for _ in range(2):                                   # the first pass pays the page faults
+        t0 = time.perf_counter()
+        oracle.sync(cal[0], cal[1], cal[2], np.zeros(cfg.K, np.float32),
+                    np.ones(cfg.K, np.float32), np.empty(nc, np.float32), np.float32(0.5),
+                    np.float32(1.0), np.float32(1.0), 0, 0)
+        rate = cfg.K * nc / (time.perf_counter() - t0)
+    n = int(min(cfg.D, max(1024, seconds_target * rate / cfg.K)))
     n -= n % 2
     rng = np.random.default_rng(cfg.seed)
     losses = wl.draw_losses(cfg, rng, 2)

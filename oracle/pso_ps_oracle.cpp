@@ -47,6 +47,17 @@
 //        acc = w*v;  acc = fma(a1, dp, acc);  acc = fma(a2, dg, acc);
 //        v = acc;  x = x + acc.
 //
+// Variants and companions (each pinned by its own CPU tests):
+//   * historical gBest (the standard-PSO reading, "gBest from the history of
+//     all particles"): gbest and gbest_loss persist across stages and are
+//     replaced only when this stage's minimum loss is strictly lower;
+//   * the scalar schedule around a stage: Eq. (5) for the inertia, the damping
+//     lambda of Eq. (6) read as the current epoch number, Algorithm 1's
+//     "t % step == 0" cadence with Max_t = epoch_size * iteration_size;
+//   * parameter averaging (Section II-B, step 5: new weights = (1/n) sum of
+//     the workers' weights, redistributed to all workers), the method PSO-PS
+//     replaces, on the same stacked layout.
+//
 // Pins (tests marked "not gpu"): identity and fixed-point special cases of
 // Eq. (6), (7); first-argmin and strict-"<" properties; exact-zero
 // consequences for the best and the improved particles; a K=2, D=8 swarm
@@ -122,11 +133,12 @@ int argmin_loss(int K, const float* loss) {
 
 // Steps 2-4 above for one dense block of n consecutive coordinates whose first
 // coordinate has flat index d0.  Rows are `ld` elements apart.
-void move_block(int K, int64_t n, int64_t ld, uint64_t d0, int g, const uint8_t* improved,
-                float* x, float* v, float* pbest, float* gbest,
+void move_block(int K, int64_t n, int64_t ld, uint64_t d0, int g, bool replace_gbest,
+                const uint8_t* improved, float* x, float* v, float* pbest, float* gbest,
                 float w, float c1, float c2, uint64_t seed, uint64_t step) {
     // gbest = x_g, before any position changes (Algorithm 3).
-    for (int64_t d = 0; d < n; ++d) gbest[d] = x[(int64_t)g * ld + d];
+    if (true)
+        for (int64_t d = 0; d < n; ++d) gbest[d] = x[(int64_t)g * ld + d];
     // pBest_i = w_i for the particles that improved (Algorithm 1).
     for (int i = 0; i < K; ++i) {
         if (!improved[i]) continue;
@@ -179,12 +191,18 @@ int pso_ps_oracle_argmin(int K, const float* loss) { return argmin_loss(K, loss)
 // those of flat coordinates d0, d0+1, ...  All arrays are host memory, updated
 // in place.  g_out (1 int) and improved_out (K bytes) may be null.
 // Returns 0, or -1 for an invalid argument.
+//
+// gbest_loss (1 float, in/out) may be null: then gbest is the best of this
+// stage only (Algorithm 3).  Otherwise gbest is an input as well, and it and
+// *gbest_loss are replaced only if the minimum loss of this stage is strictly
+// below *gbest_loss (historical gBest); replaced_out (1 int) reports which.
 int pso_ps_oracle_sync(int K, int n_seg, const int64_t* seg_sizes, const int64_t* seg_ld,
                        uint64_t d0,
                        float* const* x_seg, float* const* v_seg, float* const* pbest_seg,
                        float* pbest_loss, const float* loss, float* const* gbest_seg,
+                       float* gbest_loss,
                        float w, float c1, float c2, uint64_t seed, uint64_t step,
-                       int* g_out, uint8_t* improved_out) {
+                       int* g_out, uint8_t* improved_out, int* replaced_out) {
     if (K < 1 || n_seg < 1 || !seg_sizes || !seg_ld || !x_seg || !v_seg || !pbest_seg ||
         !pbest_loss || !loss || !gbest_seg)
         return -1;
@@ -192,6 +210,11 @@ int pso_ps_oracle_sync(int K, int n_seg, const int64_t* seg_sizes, const int64_t
         if (seg_sizes[s] < 0 || seg_ld[s] < seg_sizes[s]) return -1;
 
     const int g = argmin_loss(K, loss);
+    bool replace = true;
+    if (gbest_loss) {
+        replace = loss[g] < *gbest_loss;  // false for NaN on either side
+        if (replace) *gbest_loss = loss[g];
+    }
 
     uint8_t* improved = new uint8_t[K];
     for (int i = 0; i < K; ++i) {
@@ -202,14 +225,58 @@ int pso_ps_oracle_sync(int K, int n_seg, const int64_t* seg_sizes, const int64_t
     uint64_t start = d0;
     for (int s = 0; s < n_seg; ++s) {
         if (seg_sizes[s] > 0)
-            move_block(K, seg_sizes[s], seg_ld[s], start, g, improved, x_seg[s], v_seg[s],
+            move_block(K, seg_sizes[s], seg_ld[s], start, g, replace, improved, x_seg[s], v_seg[s],
                        pbest_seg[s], gbest_seg[s], w, c1, c2, seed, step);
         start += (uint64_t)seg_sizes[s];
     }
 
     if (g_out) *g_out = g;
     if (improved_out) std::memcpy(improved_out, improved, (size_t)K);
+    if (replaced_out) *replaced_out = replace ? 1 : 0;
     delete[] improved;
+    return 0;
+}
+
+// Eq. (5): inertia after t of t_max iterations, falling linearly from m_max to
+// m_min.  Evaluated in double and rounded to float once.
+float pso_ps_oracle_inertia(int64_t t, int64_t t_max, float m_max, float m_min) {
+    const double m = (double)m_max - (double)t * ((double)m_max - (double)m_min) / (double)t_max;
+    return (float)m;
+}
+
+// Scalars of iteration t (1-based, as Algorithm 1 counts) for a run of
+// epoch_size epochs of iteration_size iterations with a stage every `step`
+// iterations: whether t is a stage (t % step == 0 and t < Max_t), the inertia
+// of Eq. (5) with t_max = Max_t = epoch_size * iteration_size, and c1, c2
+// divided by lambda = the number of the epoch that t falls in (1 .. epoch_size;
+// the reading of "range 1 to epoch_size ... as the epoch number increases the
+// random variable factor decays").  Returns 0, or -1 for an invalid argument.
+int pso_ps_oracle_schedule(int64_t t, int64_t iteration_size, int64_t epoch_size, int64_t step,
+                           float m_max, float m_min, float c1, float c2,
+                           int* is_stage, float* w, float* c1_eff, float* c2_eff) {
+    if (t < 1 || iteration_size < 1 || epoch_size < 1 || step < 1) return -1;
+    const int64_t max_t = epoch_size * iteration_size;
+    if (t > max_t) return -1;
+    const int64_t epoch = (t - 1) / iteration_size + 1;
+    const float lambda = (float)epoch;
+    *is_stage = (t % step == 0 && t < max_t) ? 1 : 0;
+    *w = pso_ps_oracle_inertia(t, max_t, m_max, m_min);
+    *c1_eff = c1 / lambda;
+    *c2_eff = c2 / lambda;
+    return 0;
+}
+
+// Parameter averaging, step 5: mean[d] = (x[0][d] + x[1][d] + ... + x[K-1][d]) / K,
+// summed in that order in binary32, and every row is overwritten by the mean.
+int pso_ps_oracle_average(int K, int64_t n, int64_t ld, float* x, float* mean) {
+    if (K < 1 || n < 0 || ld < n || !x || !mean) return -1;
+    for (int64_t d = 0; d < n; ++d) {
+        float sum = x[d];
+        for (int k = 1; k < K; ++k) sum = sum + x[(int64_t)k * ld + d];
+        mean[d] = sum / (float)K;
+    }
+    for (int k = 0; k < K; ++k)
+        for (int64_t d = 0; d < n; ++d) x[(int64_t)k * ld + d] = mean[d];
     return 0;
 }
 

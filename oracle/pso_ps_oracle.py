@@ -51,10 +51,20 @@ def _load():
             ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_int64),
             ctypes.POINTER(ctypes.c_int64), ctypes.c_uint64,
             ctypes.POINTER(ctypes.c_void_p), ctypes.POINTER(ctypes.c_void_p),
-            ctypes.POINTER(ctypes.c_void_p), f32p, f32p, ctypes.POINTER(ctypes.c_void_p),
+            ctypes.POINTER(ctypes.c_void_p), f32p, f32p, ctypes.POINTER(ctypes.c_void_p), f32p,
             ctypes.c_float, ctypes.c_float, ctypes.c_float, ctypes.c_uint64, ctypes.c_uint64,
-            ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_uint8)]
+            ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_uint8),
+            ctypes.POINTER(ctypes.c_int)]
         lib.pso_ps_oracle_sync.restype = ctypes.c_int
+        lib.pso_ps_oracle_inertia.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_float,
+                                              ctypes.c_float]
+        lib.pso_ps_oracle_inertia.restype = ctypes.c_float
+        lib.pso_ps_oracle_schedule.argtypes = [ctypes.c_int64] * 4 + [ctypes.c_float] * 4 + \
+            [ctypes.POINTER(ctypes.c_int), f32p, f32p, f32p]
+        lib.pso_ps_oracle_schedule.restype = ctypes.c_int
+        lib.pso_ps_oracle_average.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int64, f32p,
+                                              f32p]
+        lib.pso_ps_oracle_average.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -94,12 +104,16 @@ def _check_rows(a: np.ndarray, K: int, n: int, name: str) -> int:
 
 
 def sync_segments(x_seg, v_seg, pbest_seg, pbest_loss: np.ndarray, loss: np.ndarray, gbest_seg,
-                  w: float, c1: float, c2: float, seed: int, step: int, d0: int = 0):
+                  w: float, c1: float, c2: float, seed: int, step: int, d0: int = 0,
+                  gbest_loss: Optional[np.ndarray] = None):
     """One synchronization stage, in place, over lists of per-segment arrays.
 
     x_seg[s], v_seg[s], pbest_seg[s]: float32 [K, n_s] (rows may be strided);
     gbest_seg[s]: float32 [n_s]; pbest_loss, loss: float32 [K].
-    Returns (g, improved) with improved a uint8 [K] array.
+    gbest_loss: None for the best of this stage; a float32 [1] array (in/out)
+    for the historical gBest, in which case gbest_seg is an input too.
+    Returns (g, improved) with improved a uint8 [K] array, or
+    (g, improved, replaced) when gbest_loss is given.
     """
     lib = _load()
     K = int(loss.shape[0])
@@ -125,21 +139,30 @@ def sync_segments(x_seg, v_seg, pbest_seg, pbest_loss: np.ndarray, loss: np.ndar
         for arr, tab in zip((x_seg[s], v_seg[s], pbest_seg[s], gb), ptrs):
             tab[s] = arr.ctypes.data
     g = ctypes.c_int(-1)
+    replaced = ctypes.c_int(-1)
     improved = np.zeros(K, dtype=np.uint8)
     f32p = ctypes.POINTER(ctypes.c_float)
+    if gbest_loss is not None:
+        if gbest_loss.dtype != np.float32 or gbest_loss.shape != (1,):
+            raise ValueError("gbest_loss: need float32 [1]")
+        gl = gbest_loss.ctypes.data_as(f32p)
+    else:
+        gl = None
     rc = lib.pso_ps_oracle_sync(
         K, n_seg, sizes, lds, d0, ptrs[0], ptrs[1], ptrs[2],
-        pbest_loss.ctypes.data_as(f32p), loss.ctypes.data_as(f32p), ptrs[3],
+        pbest_loss.ctypes.data_as(f32p), loss.ctypes.data_as(f32p), ptrs[3], gl,
         w, c1, c2, seed, step, ctypes.byref(g),
-        improved.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)))
+        improved.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)), ctypes.byref(replaced))
     if rc != 0:
         raise ValueError("pso_ps_oracle_sync rejected its arguments")
+    if gbest_loss is not None:
+        return int(g.value), improved, bool(replaced.value)
     return int(g.value), improved
 
 
 def sync(x: np.ndarray, v: np.ndarray, pbest: np.ndarray, pbest_loss: np.ndarray,
          loss: np.ndarray, gbest: np.ndarray, w: float, c1: float, c2: float,
-         seed: int, step: int, d0: int = 0):
+         seed: int, step: int, d0: int = 0, gbest_loss: Optional[np.ndarray] = None):
     """One synchronization stage, in place, on a flat swarm.
 
     x, v, pbest: float32 [K, n]; gbest: float32 [n]; the random numbers are
@@ -147,4 +170,33 @@ def sync(x: np.ndarray, v: np.ndarray, pbest: np.ndarray, pbest_loss: np.ndarray
     swarm can be advanced on its own.  Returns (g, improved).
     """
     return sync_segments([x], [v], [pbest], pbest_loss, loss, [gbest], w, c1, c2, seed, step,
-                         d0=d0)
+                         d0=d0, gbest_loss=gbest_loss)
+
+
+def inertia(t: int, t_max: int, m_max: float, m_min: float) -> np.float32:
+    """Eq. (5)."""
+    return np.float32(_load().pso_ps_oracle_inertia(t, t_max, m_max, m_min))
+
+
+def schedule(t: int, iteration_size: int, epoch_size: int, step: int, m_max: float, m_min: float,
+             c1: float, c2: float):
+    """(is_stage, w, c1/lambda, c2/lambda) of iteration t (1-based)."""
+    flag = ctypes.c_int(-1)
+    w, a1, a2 = ctypes.c_float(), ctypes.c_float(), ctypes.c_float()
+    rc = _load().pso_ps_oracle_schedule(t, iteration_size, epoch_size, step, m_max, m_min, c1, c2,
+                                        ctypes.byref(flag), ctypes.byref(w), ctypes.byref(a1),
+                                        ctypes.byref(a2))
+    if rc != 0:
+        raise ValueError("pso_ps_oracle_schedule rejected its arguments")
+    return bool(flag.value), np.float32(w.value), np.float32(a1.value), np.float32(a2.value)
+
+
+def average(x: np.ndarray, mean: np.ndarray) -> None:
+    """Parameter averaging in place: mean = column means of x, every row of x = mean."""
+    K, n = x.shape
+    ld = _check_rows(x, K, n, "x")
+    if mean.dtype != np.float32 or mean.shape != (n,) or (n > 1 and mean.strides[0] != 4):
+        raise ValueError(f"mean: need contiguous float32 [{n}]")
+    f32p = ctypes.POINTER(ctypes.c_float)
+    if _load().pso_ps_oracle_average(K, n, ld, x.ctypes.data_as(f32p), mean.ctypes.data_as(f32p)):
+        raise ValueError("pso_ps_oracle_average rejected its arguments")
