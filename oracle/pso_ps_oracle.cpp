@@ -137,7 +137,7 @@ void move_block(int K, int64_t n, int64_t ld, uint64_t d0, int g, bool replace_g
                 const uint8_t* improved, float* x, float* v, float* pbest, float* gbest,
                 float w, float c1, float c2, uint64_t seed, uint64_t step) {
     // gbest = x_g, before any position changes (Algorithm 3).
-    if (true)
+    if (replace_gbest)
         for (int64_t d = 0; d < n; ++d) gbest[d] = x[(int64_t)g * ld + d];
     // pBest_i = w_i for the particles that improved (Algorithm 1).
     for (int i = 0; i < K; ++i) {
