@@ -103,6 +103,49 @@ int pso_ps_sync_segments(pso_ps_ctx* h, float* const* x_seg, float* const* v_seg
                          float* const* gbest_seg, float w, float c1, float c2,
                          uint64_t seed, uint64_t step, void* hip_stream);
 
+/* The stage with the historical global best, the reading of the standard PSO
+ * framework (Section II-C, step 3: gBest "from the history of all particles"):
+ * gbest (device [D]) and gbest_loss (device, 1 float) are in/out and persist
+ * across stages; they are replaced by x_g and loss_g only if loss_g is
+ * strictly below *gbest_loss (a NaN never replaces).  Start with
+ * *gbest_loss = +inf.  Everything else as pso_ps_sync; in a stage that keeps
+ * the old gbest, this stage's best particle is pulled towards it too. */
+int pso_ps_sync_history(pso_ps_ctx* h, float* x, float* v, float* pbest,
+                        float* pbest_loss, const float* loss, float* gbest,
+                        float* gbest_loss, float w, float c1, float c2,
+                        uint64_t seed, uint64_t step, void* hip_stream);
+
+/* The stage on K separate per-worker arrays instead of one stacked buffer: the
+ * single-GPU stand-in for Algorithm 3's gather and Algorithm 1's "distribute
+ * new weights", with no packing copy.  x_rows, v_rows, pbest_rows are HOST
+ * arrays of K device pointers, row i holding D floats; ld of the handle is
+ * ignored.  Bitwise the same result as pso_ps_sync on the stacked rows. */
+int pso_ps_sync_rows(pso_ps_ctx* h, float* const* x_rows, float* const* v_rows,
+                     float* const* pbest_rows, float* pbest_loss, const float* loss,
+                     float* gbest, float w, float c1, float c2,
+                     uint64_t seed, uint64_t step, void* hip_stream);
+
+/* Parameter averaging (Section II-B, step 5), the synchronization PSO-PS
+ * replaces, on the same stacked layout: mean[d] = (x[0][d] + ... + x[K-1][d]) / K,
+ * summed in that order in binary32, written to `mean` (device [D]) and to
+ * every row of x (device [K, ld], in/out). */
+int pso_ps_average(pso_ps_ctx* h, float* x, float* mean, void* hip_stream);
+
+/* Eq. (5): inertia after t of t_max iterations, falling linearly from m_max to
+ * m_min; evaluated in double, rounded to float once.  Host function. */
+float pso_ps_inertia(int64_t t, int64_t t_max, float m_max, float m_min);
+
+/* Host-side scalars of iteration t (1-based, as Algorithm 1 counts) of a run
+ * of epoch_size epochs with iteration_size iterations each and a stage every
+ * `step` iterations: *is_stage = (t % step == 0 and t < Max_t), Max_t =
+ * epoch_size * iteration_size; *w = Eq. (5) with t_max = Max_t; *c1_eff =
+ * c1 / lambda, *c2_eff = c2 / lambda with lambda = the number (1 .. epoch_size)
+ * of the epoch t falls in.  Table II: m_max 0.9, m_min 0.3, c1 0.2, c2 0.9.
+ * PSO_PS_EINVAL for t outside 1 .. Max_t or a non-positive size. */
+int pso_ps_schedule(int64_t t, int64_t iteration_size, int64_t epoch_size, int64_t step,
+                    float m_max, float m_min, float c1, float c2,
+                    int* is_stage, float* w, float* c1_eff, float* c2_eff);
+
 /* Global search and personal-best test (steps 1, 2 and the test of step 3):
  * g = argmin loss and gbest = x_g, i.e. what Algorithm 3 returns, plus
  * improved_i = loss_i < pbest_loss_i and pbest_loss_i = min(pbest_loss_i,
@@ -120,11 +163,12 @@ int pso_ps_update(pso_ps_ctx* h, float* x, float* v, float* pbest, const float* 
                   void* hip_stream);
 
 /* Read back the last selection: waits for the stream of the last call on this
- * handle, then writes g to *g_out and the improved flags, bit i of word i/64,
- * to improved_mask_out[0..mask_words-1] (host; mask_words >= (K+63)/64).
- * Either output may be NULL.  For tests and logging, not for the hot path. */
+ * handle, then writes g to *g_out, the improved flags, bit i of word i/64, to
+ * improved_mask_out[0..mask_words-1] (host; mask_words >= (K+63)/64), and to
+ * *replaced_out whether gbest was (re)written (always 1 without history).
+ * Any output may be NULL.  For tests and logging, not for the hot path. */
 int pso_ps_last_selection(pso_ps_ctx* h, int* g_out, uint64_t* improved_mask_out,
-                          int mask_words);
+                          int mask_words, int* replaced_out);
 
 /* Launch shape of the update kernel, for measurement and tests; results are
  * bitwise independent of all of it.  0 selects the library default.

@@ -51,13 +51,23 @@ def load():
     lib.pso_ps_sync_segments.argtypes = [P, PP, PP, PP, _f32p, _f32p, PP, F, F, F, U64, U64, P]
     lib.pso_ps_select.argtypes = [P, _f32p, _f32p, _f32p, _f32p, P]
     lib.pso_ps_update.argtypes = [P, _f32p, _f32p, _f32p, _f32p, F, F, F, U64, U64, P]
-    lib.pso_ps_last_selection.argtypes = [P, ctypes.POINTER(I), ctypes.POINTER(U64), I]
+    lib.pso_ps_last_selection.argtypes = [P, ctypes.POINTER(I), ctypes.POINTER(U64), I,
+                                          ctypes.POINTER(I)]
+    lib.pso_ps_sync_history.argtypes = [P, _f32p, _f32p, _f32p, _f32p, _f32p, _f32p, _f32p,
+                                        F, F, F, U64, U64, P]
+    lib.pso_ps_sync_rows.argtypes = [P, PP, PP, PP, _f32p, _f32p, _f32p, F, F, F, U64, U64, P]
+    lib.pso_ps_average.argtypes = [P, _f32p, _f32p, P]
+    lib.pso_ps_inertia.argtypes = [I64, I64, F, F]
+    lib.pso_ps_inertia.restype = F
+    lib.pso_ps_schedule.argtypes = [I64, I64, I64, I64, F, F, F, F, ctypes.POINTER(I),
+                                    ctypes.POINTER(F), ctypes.POINTER(F), ctypes.POINTER(F)]
     lib.pso_ps_set_launch.argtypes = [P, I, I, I, I]
     lib.pso_ps_last_hip_error.argtypes = [P]
     lib.pso_ps_destroy.argtypes = [P]
     lib.pso_ps_strerror.argtypes = [I]
     for name in ("pso_ps_create", "pso_ps_sync", "pso_ps_sync_segments", "pso_ps_select",
                  "pso_ps_update", "pso_ps_last_selection", "pso_ps_set_launch",
+                 "pso_ps_sync_history", "pso_ps_sync_rows", "pso_ps_average", "pso_ps_schedule",
                  "pso_ps_last_hip_error", "pso_ps_destroy"):
         getattr(lib, name).restype = I
     lib.pso_ps_strerror.restype = ctypes.c_char_p
@@ -135,13 +145,54 @@ def pso_ps_update(h: int, x, v, pbest, gbest, w: float, c1: float, c2: float, se
     _check(rc, "pso_ps_update", h)
 
 
-def pso_ps_last_selection(h: int, K: int):
-    """(g, improved) with improved a list of K bools.  Waits for the stream."""
+def pso_ps_last_selection(h: int, K: int, with_replaced: bool = False):
+    """(g, improved) with improved a list of K bools, plus whether gbest was
+    rewritten if with_replaced.  Waits for the stream."""
     words = (K + 63) // 64
-    g = ctypes.c_int(-1)
+    g, replaced = ctypes.c_int(-1), ctypes.c_int(-1)
     mask = (ctypes.c_uint64 * words)()
-    _check(load().pso_ps_last_selection(h, ctypes.byref(g), mask, words), "pso_ps_last_selection", h)
-    return int(g.value), [bool((mask[i >> 6] >> (i & 63)) & 1) for i in range(K)]
+    _check(load().pso_ps_last_selection(h, ctypes.byref(g), mask, words, ctypes.byref(replaced)),
+           "pso_ps_last_selection", h)
+    improved = [bool((mask[i >> 6] >> (i & 63)) & 1) for i in range(K)]
+    if with_replaced:
+        return int(g.value), improved, bool(replaced.value)
+    return int(g.value), improved
+
+
+def pso_ps_sync_history(h: int, x, v, pbest, pbest_loss, loss, gbest, gbest_loss, w: float, c1: float,
+                        c2: float, seed: int, step: int, stream=None) -> None:
+    rc = load().pso_ps_sync_history(h, _addr(x), _addr(v), _addr(pbest), _addr(pbest_loss),
+                                    _addr(loss), _addr(gbest), _addr(gbest_loss), w, c1, c2,
+                                    seed, step, _stream(stream))
+    _check(rc, "pso_ps_sync_history", h)
+
+
+def pso_ps_sync_rows(h: int, x_rows, v_rows, pbest_rows, pbest_loss, loss, gbest, w: float,
+                     c1: float, c2: float, seed: int, step: int, stream=None) -> None:
+    rc = load().pso_ps_sync_rows(h, _table(x_rows), _table(v_rows), _table(pbest_rows),
+                                 _addr(pbest_loss), _addr(loss), _addr(gbest), w, c1, c2,
+                                 seed, step, _stream(stream))
+    _check(rc, "pso_ps_sync_rows", h)
+
+
+def pso_ps_average(h: int, x, mean, stream=None) -> None:
+    _check(load().pso_ps_average(h, _addr(x), _addr(mean), _stream(stream)), "pso_ps_average", h)
+
+
+def pso_ps_inertia(t: int, t_max: int, m_max: float, m_min: float) -> float:
+    return float(load().pso_ps_inertia(t, t_max, m_max, m_min))
+
+
+def pso_ps_schedule(t: int, iteration_size: int, epoch_size: int, step: int, m_max: float,
+                    m_min: float, c1: float, c2: float):
+    """(is_stage, w, c1/lambda, c2/lambda) of iteration t (1-based)."""
+    flag = ctypes.c_int(-1)
+    w, a1, a2 = ctypes.c_float(), ctypes.c_float(), ctypes.c_float()
+    rc = load().pso_ps_schedule(t, iteration_size, epoch_size, step, m_max, m_min, c1, c2,
+                                ctypes.byref(flag), ctypes.byref(w), ctypes.byref(a1),
+                                ctypes.byref(a2))
+    _check(rc, "pso_ps_schedule")
+    return bool(flag.value), float(w.value), float(a1.value), float(a2.value)
 
 
 def pso_ps_set_launch(h: int, block_threads: int = 0, super_tiles: int = 0, chunk_tiles: int = 0,

@@ -55,7 +55,9 @@ typedef float f32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));
 
 // Device scratch owned by a handle.
 struct Selection {
-    int g;                 // index of the global best particle
+    int g;                 // index of this stage's best particle
+    int replaced;          // 1 if this stage's selection (re)wrote gbest
+    float gbest_loss;      // historical gBest: the loss that goes with gbest after this stage
     int reserved;
     uint64_t improved[1];  // bit i of word i/64: particle i improved (really (K+63)/64 words)
 };
@@ -70,6 +72,22 @@ struct ColumnBlock {
     long long ld;
     long long n;
     unsigned long long d0;
+};
+
+// Row-pointer mode: the K particles are K separate arrays (each worker's own
+// weight tensor); one launch carries at most kTableRows of them by value.
+constexpr int kTableRows = 32;
+struct RowTable {
+    float* x[kTableRows];
+    float* v[kTableRows];
+    float* pbest[kTableRows];
+};
+
+// Start of one particle's row in x, v and pbest.
+struct RowPtrs {
+    float* x;
+    float* v;
+    float* pbest;
 };
 
 struct MoveParams {
@@ -145,44 +163,44 @@ __device__ __forceinline__ bool is_improved(const Selection* __restrict__ sel, i
 }
 
 // One element of one row, element-wise accesses: ragged row ends and the
-// generic path.  `col` is the column inside the block, `row` the row offset.
-__device__ __forceinline__ void move_single(const ColumnBlock& b, long long row, long long col, int i,
+// generic path.  `col` is the column inside the block.
+__device__ __forceinline__ void move_single(const RowPtrs& r, const float* __restrict__ gbest,
+                                            unsigned long long d0, long long col, unsigned i,
                                             bool improved, const MoveParams& m) {
-    const unsigned long long d = b.d0 + (unsigned long long)col;
-    const Words4 r = philox4x32_10((uint32_t)(d >> 1), (uint32_t)i, m.step_lo, m.step_hi,
-                                   m.key0, m.key1);
-    const long long at = row + col;
-    float xv = b.x[at];
-    float vv = b.v[at];
-    const float pv = improved ? xv : b.pbest[at];
-    if (improved) b.pbest[at] = xv;
+    const unsigned long long d = d0 + (unsigned long long)col;
+    const Words4 words = philox4x32_10((uint32_t)(d >> 1), i, m.step_lo, m.step_hi, m.key0, m.key1);
+    float xv = r.x[col];
+    float vv = r.v[col];
+    const float pv = improved ? xv : r.pbest[col];
+    if (improved) r.pbest[col] = xv;
     const bool odd = d & 1ull;
-    move_element(xv, vv, pv, b.gbest[col], odd ? r.s2 : r.s0, odd ? r.s3 : r.s1, m);
-    b.x[at] = xv;
-    b.v[at] = vv;
+    move_element(xv, vv, pv, gbest[col], odd ? words.s2 : words.s0, odd ? words.s3 : words.s1, m);
+    r.x[col] = xv;
+    r.v[col] = vv;
 }
 
 // Columns c .. c+3 of row i with 128-bit accesses (the addresses are 16-byte
 // aligned in x, v and pbest, and d0 + c is even).  improved (uniform over the
 // workgroup): Algorithm 1 replaced this particle's personal best by its
 // position, so pbest is written instead of read.
-__device__ __forceinline__ void move_quad(const ColumnBlock& b, long long row, long long c,
-                                          unsigned i, bool improved, const MoveParams& m) {
-    float* xp = b.x + row + c;
-    float* vp = b.v + row + c;
-    float* pp = b.pbest + row + c;
+__device__ __forceinline__ void move_quad(const RowPtrs& r, const float* __restrict__ gbest,
+                                          unsigned long long d0, long long c, unsigned i,
+                                          bool improved, const MoveParams& m) {
+    float* xp = r.x + c;
+    float* vp = r.v + c;
+    float* pp = r.pbest + c;
     f32x4 x_old = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(xp));
     f32x4 v_old = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(vp));
     f32x4 p_old = {0.0f, 0.0f, 0.0f, 0.0f};
     if (!improved) p_old = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(pp));
-    f32x4 gb = *reinterpret_cast<const f32x4_a4*>(b.gbest + c);
+    f32x4 gb = *reinterpret_cast<const f32x4_a4*>(gbest + c);
     __builtin_amdgcn_sched_barrier(0);  // all four loads are issued before anything below
 
     // The random words need nothing from memory: compute them while the loads
     // are in flight.  The empty asm ties the loaded values to the last random
     // words, which keeps the compiler from moving any use of them (and the
     // wait that goes with it) in front of the Philox rounds.
-    const uint32_t pair = (uint32_t)((b.d0 + (unsigned long long)c) >> 1);
+    const uint32_t pair = (uint32_t)((d0 + (unsigned long long)c) >> 1);
     const Words4 ra = philox4x32_10(pair, i, m.step_lo, m.step_hi, m.key0, m.key1);
     const Words4 rb = philox4x32_10(pair + 1u, i, m.step_lo, m.step_hi, m.key0, m.key1);
     asm volatile("" : "+v"(x_old), "+v"(v_old), "+v"(p_old), "+v"(gb) : "v"(ra.s0), "v"(rb.s0));
@@ -199,25 +217,19 @@ __device__ __forceinline__ void move_quad(const ColumnBlock& b, long long row, l
     if (improved) __builtin_nontemporal_store(x_old, reinterpret_cast<f32x4*>(pp));
 }
 
-// Update pass.  VEC: x, v, pbest are congruent modulo 16 bytes, rows are an even
-// number of elements apart and (d0 + element address of x) is even, so that an
-// address-aligned group of four floats is two whole Philox pairs.  Otherwise
-// (VEC = false) tiles start at column 0 and everything is element-wise.
-template <int BLOCK, bool VEC>
-__global__ __launch_bounds__(BLOCK) void update_kernel(ColumnBlock b, int K,
-                                                       const Selection* __restrict__ sel,
-                                                       MoveParams m, TileOrder ord) {
-    constexpr unsigned TILE = BLOCK * 4;
-    // -- which (row, tile) is this workgroup? ---------------------------------
+// Which (row, tile) does this workgroup handle?  `rows` rows share the order.
+// Returns false for the padding workgroups at the end of an XCD's list.
+__device__ __forceinline__ bool decode_workgroup(const TileOrder& ord, unsigned rows,
+                                                 unsigned* row, unsigned* tile) {
     const unsigned xcd = blockIdx.x & 7u;
     const unsigned j = blockIdx.x >> 3;
     const unsigned super = 1u << ord.super_log2;
-    const unsigned full_span = (ord.full << ord.super_log2) * (unsigned)K;
+    const unsigned full_span = (ord.full << ord.super_log2) * rows;
     unsigned i, u;
     if (j < full_span) {
-        const unsigned q = j >> ord.super_log2;        // (super-chunk, row) pair
-        const unsigned sc = q / (unsigned)K;
-        i = q - sc * (unsigned)K;
+        const unsigned q = j >> ord.super_log2;  // (super-chunk, row) pair
+        const unsigned sc = q / rows;
+        i = q - sc * rows;
         u = (sc << ord.super_log2) + (j & (super - 1u));
     } else {
         const unsigned r = j - full_span;
@@ -225,82 +237,191 @@ __global__ __launch_bounds__(BLOCK) void update_kernel(ColumnBlock b, int K,
         u = (ord.full << ord.super_log2) + (r - i * ord.last);
     }
     const unsigned chunk_mask = (1u << ord.chunk_log2) - 1u;
-    const unsigned t = ((((u >> ord.chunk_log2) << 3) + xcd) << ord.chunk_log2) + (u & chunk_mask);
-    if (t >= ord.tiles || i >= (unsigned)K) return;
+    *tile = ((((u >> ord.chunk_log2) << 3) + xcd) << ord.chunk_log2) + (u & chunk_mask);
+    *row = i;
+    return *tile < ord.tiles && i < rows;
+}
 
-    // -- which columns? tiles are aligned to the address of the row -----------
-    const long long row = (long long)i * b.ld;
+// One row x one tile.  VEC: x, v, pbest of the row are congruent modulo 16
+// bytes and (d0 + element address of x) is even, so that an address-aligned
+// group of four floats is two whole Philox pairs; tiles are then aligned to the
+// address of the row.  Otherwise tiles start at column 0 and everything is
+// element-wise.
+template <int BLOCK, bool VEC>
+__device__ __forceinline__ void update_tile(const RowPtrs& r, const float* __restrict__ gbest,
+                                            long long n, unsigned long long d0, unsigned i,
+                                            unsigned tile, bool improved, const MoveParams& m) {
+    constexpr unsigned TILE = BLOCK * 4;
     long long phase = 0;
-    if (VEC) phase = (long long)((reinterpret_cast<uintptr_t>(b.x + row) >> 2) & (TILE - 1u));
-    const long long c = (long long)t * TILE - phase + 4 * (long long)threadIdx.x;
-    if (c + 4 <= 0 || c >= b.n) return;
-    const bool improved = is_improved(sel, (int)i);
-
-    if (VEC && c >= 0 && c + 4 <= b.n) {
-        move_quad(b, row, c, i, improved, m);
+    if (VEC) phase = (long long)((reinterpret_cast<uintptr_t>(r.x) >> 2) & (TILE - 1u));
+    const long long c = (long long)tile * TILE - phase + 4 * (long long)threadIdx.x;
+    if (c + 4 <= 0 || c >= n) return;
+    if (VEC && c >= 0 && c + 4 <= n) {
+        move_quad(r, gbest, d0, c, i, improved, m);
     } else {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const long long col = c + e;
-            if (col >= 0 && col < b.n) move_single(b, row, col, (int)i, improved, m);
+            if (col >= 0 && col < n) move_single(r, gbest, d0, col, i, improved, m);
         }
     }
 }
 
-// Selection and gbest copy.  With do_select every wavefront finds g on its own
-// from the K losses (lexicographic minimum of (loss, index), NaN read as +inf:
-// the first argmin of Algorithm 3); wavefront 0 of workgroup 0 also applies the
-// strict "<" test of Algorithm 1 against pbest_loss and publishes g and the
-// improved mask.  Nobody but that wavefront touches pbest_loss, and nobody
-// reads what it writes, so there is no ordering problem inside the launch.
-// Without do_select g is read from the handle's scratch.  Then gbest = x_g.
-template <int BLOCK>
+// Update pass over stacked [K, ld] arrays.  gbest_loss (may be null) is the
+// caller's historical-gBest loss: the selection kernel only reads it, and the
+// value that belongs to this stage is stored here, after that kernel is done.
+template <int BLOCK, bool VEC>
+__global__ __launch_bounds__(BLOCK) void update_kernel(ColumnBlock b, int K,
+                                                       const Selection* __restrict__ sel,
+                                                       MoveParams m, TileOrder ord,
+                                                       float* gbest_loss) {
+    if (gbest_loss && blockIdx.x == 0 && threadIdx.x == 0) *gbest_loss = sel->gbest_loss;
+    unsigned i, tile;
+    if (!decode_workgroup(ord, (unsigned)K, &i, &tile)) return;
+    const long long row = (long long)i * b.ld;
+    const RowPtrs r{b.x + row, b.v + row, b.pbest + row};
+    update_tile<BLOCK, VEC>(r, b.gbest, b.n, b.d0, i, tile, is_improved(sel, (int)i), m);
+}
+
+// Update pass over `rows` separate particle arrays, particles row0 .. row0+rows-1.
+template <int BLOCK, bool VEC>
+__global__ __launch_bounds__(BLOCK) void update_rows_kernel(RowTable tab, const float* gbest,
+                                                            long long n, int row0, int rows,
+                                                            const Selection* __restrict__ sel,
+                                                            MoveParams m, TileOrder ord) {
+    unsigned i, tile;
+    if (!decode_workgroup(ord, (unsigned)rows, &i, &tile)) return;
+    const RowPtrs r{tab.x[i], tab.v[i], tab.pbest[i]};
+    const unsigned particle = (unsigned)row0 + i;
+    update_tile<BLOCK, VEC>(r, gbest, n, 0ull, particle, tile, is_improved(sel, (int)particle), m);
+}
+
+// Where the gbest copy finds row g: in a stacked array, or among the rows that
+// a row-pointer launch carries (null if g is not one of them).
+struct StackedSource {
+    const float* x;
+    long long ld;
+    __device__ const float* row(int g) const { return x + (long long)g * ld; }
+};
+struct TableSource {
+    const float* x[kTableRows];
+    int row0, rows;
+    __device__ const float* row(int g) const {
+        return (g >= row0 && g < row0 + rows) ? x[g - row0] : nullptr;
+    }
+};
+
+// Lexicographic minimum of (loss, index) over the K losses with NaN read as
+// +inf: the first argmin of Algorithm 3.  Every lane returns the same result.
+// With `publisher` the calling wavefront also applies the strict "<" test of
+// Algorithm 1 against pbest_loss and stores the improved mask.
+__device__ __forceinline__ void wave_argmin(int K, const float* __restrict__ loss, float* pbest_loss,
+                                            Selection* sel, bool publisher, float* best_out,
+                                            int* g_out) {
+    const int lane = threadIdx.x & 63;
+    const float inf = __builtin_huge_valf();
+    float best = inf;
+    int best_i = 0x7fffffff;
+    for (int base = 0; base < K; base += 64) {
+        const int i = base + lane;
+        bool improved = false;
+        if (i < K) {
+            const float l = loss[i];
+            const float key = (l != l) ? inf : l;
+            if (best_i == 0x7fffffff || key < best) { best = key; best_i = i; }
+            if (publisher) {
+                improved = l < pbest_loss[i];  // false if either is NaN
+                if (improved) pbest_loss[i] = l;
+            }
+        }
+        const unsigned long long mask = __ballot(improved);
+        if (publisher && lane == 0) sel->improved[base >> 6] = mask;
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const float other = __shfl_xor(best, off, 64);
+        const int other_i = __shfl_xor(best_i, off, 64);
+        if (other < best || (other == best && other_i < best_i)) { best = other; best_i = other_i; }
+    }
+    *best_out = best;
+    *g_out = best_i;
+}
+
+// Selection and gbest copy.  With do_select every wavefront finds g on its own;
+// wavefront 0 of workgroup 0 also does the pBest test and publishes g, the
+// improved mask and whether gbest is replaced.  Nobody but that wavefront
+// touches pbest_loss or the scratch, and nobody in this launch reads what it
+// writes, so there is no ordering problem.  Without do_select, g and the
+// replace flag are read from the scratch (later segments / row groups).
+//
+// gbest_loss == null: gbest = x_g always (Algorithm 3).  Otherwise historical
+// gBest: gbest = x_g only if this stage's lowest loss is strictly below
+// *gbest_loss, which this kernel only reads.
+//
+// In row-pointer mode a launch carries some of the rows by value and copies
+// only if g is one of them.
+template <int BLOCK, class Source>
 __global__ __launch_bounds__(BLOCK) void select_gbest_kernel(int K, const float* __restrict__ loss,
                                                              float* pbest_loss, Selection* sel,
-                                                             const float* __restrict__ x,
-                                                             float* __restrict__ gbest,
-                                                             long long ld, long long n,
+                                                             Source source,
+                                                             float* __restrict__ gbest, long long n,
+                                                             const float* gbest_loss,
                                                              int do_select) {
     int g;
+    bool replace;
     if (do_select) {
-        const int lane = threadIdx.x & 63;
         const bool publisher = blockIdx.x == 0 && threadIdx.x < 64;
-        const float inf = __builtin_huge_valf();
-        float best = inf;
-        int best_i = 0x7fffffff;
-        for (int base = 0; base < K; base += 64) {
-            const int i = base + lane;
-            bool improved = false;
-            if (i < K) {
-                const float l = loss[i];
-                const float key = (l != l) ? inf : l;
-                if (best_i == 0x7fffffff || key < best) { best = key; best_i = i; }
-                if (publisher) {
-                    improved = l < pbest_loss[i];  // false if either is NaN
-                    if (improved) pbest_loss[i] = l;
-                }
-            }
-            const unsigned long long mask = __ballot(improved);
-            if (publisher && lane == 0) sel->improved[base >> 6] = mask;
+        float best;
+        wave_argmin(K, loss, pbest_loss, sel, publisher, &best, &g);
+        const float kept = gbest_loss ? *gbest_loss : 0.0f;
+        replace = gbest_loss ? (best < kept) : true;
+        if (publisher && (threadIdx.x & 63) == 0) {
+            sel->g = g;
+            sel->replaced = replace ? 1 : 0;
+            sel->gbest_loss = replace ? best : kept;
         }
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) {
-            const float other = __shfl_xor(best, off, 64);
-            const int other_i = __shfl_xor(best_i, off, 64);
-            if (other < best || (other == best && other_i < best_i)) { best = other; best_i = other_i; }
-        }
-        g = best_i;
-        if (publisher && lane == 0) sel->g = g;
     } else {
         g = sel->g;
+        replace = sel->replaced != 0;
     }
+    if (!replace) return;
+    const float* src = source.row(g);
+    if (!src) return;
     const long long c = ((long long)blockIdx.x * BLOCK + threadIdx.x) * 4;
     if (c >= n) return;
-    const float* src = x + (long long)g * ld + c;
     if (c + 4 <= n) {
-        *reinterpret_cast<f32x4_a4*>(gbest + c) = *reinterpret_cast<const f32x4_a4*>(src);
+        *reinterpret_cast<f32x4_a4*>(gbest + c) = *reinterpret_cast<const f32x4_a4*>(src + c);
     } else {
-        for (long long e = 0; c + e < n; ++e) gbest[c + e] = src[e];
+        for (long long e = c; e < n; ++e) gbest[e] = src[e];
+    }
+}
+
+// Parameter averaging (Section II-B, step 5) on the stacked layout: one thread
+// owns four columns, sums the K rows in order, divides by K, and writes the
+// mean back to every row and to `mean`.  8 K + 4 bytes per column.
+template <int BLOCK>
+__global__ __launch_bounds__(BLOCK) void average_kernel(float* x, float* __restrict__ mean,
+                                                        long long ld, long long n, int K) {
+    const long long c = ((long long)blockIdx.x * BLOCK + threadIdx.x) * 4;
+    if (c >= n) return;
+    const float kf = (float)K;
+    if (c + 4 <= n) {
+        f32x4 sum = __builtin_nontemporal_load(reinterpret_cast<const f32x4_a4*>(x + c));
+        for (int k = 1; k < K; ++k)
+            sum = sum + __builtin_nontemporal_load(
+                            reinterpret_cast<const f32x4_a4*>(x + (long long)k * ld + c));
+        const f32x4 avg = {sum.x / kf, sum.y / kf, sum.z / kf, sum.w / kf};
+        *reinterpret_cast<f32x4_a4*>(mean + c) = avg;
+        for (int k = 0; k < K; ++k)
+            __builtin_nontemporal_store(avg, reinterpret_cast<f32x4_a4*>(x + (long long)k * ld + c));
+    } else {
+        for (long long e = c; e < n; ++e) {
+            float sum = x[e];
+            for (int k = 1; k < K; ++k) sum = sum + x[(long long)k * ld + e];
+            const float avg = sum / kf;
+            mean[e] = avg;
+            for (int k = 0; k < K; ++k) x[(long long)k * ld + e] = avg;
+        }
     }
 }
 
@@ -341,6 +462,7 @@ namespace {
 constexpr int kDefaultBlock = 128;
 constexpr unsigned kDefaultSuperBytes = 2u << 20;    // gbest footprint per XCD, in its 4 MiB L2
 constexpr unsigned kDefaultChunkBytes = 256u << 10;  // consecutive addresses handed to one XCD
+constexpr int kCopyBlock = 256;                      // select_gbest_kernel, average_kernel
 
 // Makes the handle's device current for the lifetime of the object.
 struct DeviceScope {
@@ -364,41 +486,42 @@ int hip_fail(pso_ps_ctx* h, hipError_t e) {
     return PSO_PS_EHIP;
 }
 
-int check_block(const ColumnBlock& b) {
-    if (!b.x || !b.v || !b.pbest || !b.gbest) return PSO_PS_EINVAL;
-    if (!aligned_to(b.x, 4) || !aligned_to(b.v, 4) || !aligned_to(b.pbest, 4) ||
-        !aligned_to(b.gbest, 4))
+int check_arrays(const float* x, const float* v, const float* pbest, const float* gbest) {
+    if (!x || !v || !pbest || !gbest) return PSO_PS_EINVAL;
+    if (!aligned_to(x, 4) || !aligned_to(v, 4) || !aligned_to(pbest, 4) || !aligned_to(gbest, 4))
         return PSO_PS_EALIGN;
+    return PSO_PS_OK;
+}
+
+int check_block(const ColumnBlock& b) {
+    const int rc = check_arrays(b.x, b.v, b.pbest, b.gbest);
+    if (rc != PSO_PS_OK) return rc;
     if (b.n < 0 || b.ld < b.n) return PSO_PS_EINVAL;
     // Philox counter word 0 holds the pair index: flat indices must stay below 2^33.
     if (b.d0 + (unsigned long long)b.n > (1ull << 33)) return PSO_PS_EINVAL;
     return PSO_PS_OK;
 }
 
-// Can this block take the 128-bit path?  See update_kernel.
-bool vector_path_ok(const pso_ps_ctx* h, const ColumnBlock& b) {
-    if (h->force_generic) return false;
-    const uintptr_t ax = reinterpret_cast<uintptr_t>(b.x);
-    const uintptr_t av = reinterpret_cast<uintptr_t>(b.v);
-    const uintptr_t ap = reinterpret_cast<uintptr_t>(b.pbest);
+// Can one row take the 128-bit path?  x, v, pbest congruent modulo 16 bytes and
+// (element address of x + flat index of its first column) even.
+bool row_vector_ok(const float* x, const float* v, const float* pbest, unsigned long long d0) {
+    const uintptr_t ax = reinterpret_cast<uintptr_t>(x);
+    const uintptr_t av = reinterpret_cast<uintptr_t>(v);
+    const uintptr_t ap = reinterpret_cast<uintptr_t>(pbest);
     if (((ax ^ av) & 15u) || ((ax ^ ap) & 15u)) return false;
-    if (h->K > 1 && (b.ld & 1)) return false;
-    return (((ax >> 2) + b.d0) & 1ull) == 0;
+    return (((ax >> 2) + d0) & 1ull) == 0;
 }
 
-// Tiles per row and the workgroup order for one block of columns.
-// Returns false if the launch would not fit the grid limits.
-bool plan_order(const pso_ps_ctx* h, const ColumnBlock& b, bool vec, unsigned tile,
+bool block_vector_ok(const pso_ps_ctx* h, const ColumnBlock& b) {
+    if (h->force_generic) return false;
+    if (h->K > 1 && (b.ld & 1)) return false;
+    return row_vector_ok(b.x, b.v, b.pbest, b.d0);
+}
+
+// Workgroup order for `rows` rows of n columns whose address-aligned tiling
+// needs `tiles` tiles per row.  Returns false if the grid would be too large.
+bool plan_order(const pso_ps_ctx* h, int rows, unsigned long long tiles, unsigned tile,
                 TileOrder* ord, unsigned long long* grid) {
-    unsigned long long max_phase = 0;
-    if (vec) {
-        for (int i = 0; i < h->K; ++i) {
-            const unsigned long long a =
-                (reinterpret_cast<uintptr_t>(b.x + (long long)i * b.ld) >> 2) & (tile - 1u);
-            if (a > max_phase) max_phase = a;
-        }
-    }
-    const unsigned long long tiles = (max_phase + (unsigned long long)b.n + tile - 1) / tile;
     // Large blocks: XCD-aware super-chunks.  Small ones: plain row-major order,
     // which is the special case "one super-chunk, chunks of one tile".
     unsigned long long super = h->super_tiles ? (unsigned long long)h->super_tiles
@@ -406,10 +529,10 @@ bool plan_order(const pso_ps_ctx* h, const ColumnBlock& b, bool vec, unsigned ti
     unsigned long long chunk = h->chunk_tiles ? (unsigned long long)h->chunk_tiles
                                               : kDefaultChunkBytes / (tile * 4u);
     if (chunk > super) chunk = super;
-    if (tiles < 16ull * super) chunk = 1;           // keep all eight XCDs evenly loaded
+    if (tiles < 16ull * super) chunk = 1;  // keep all eight XCDs evenly loaded
     const unsigned long long per_xcd = (tiles + 8 * chunk - 1) / (8 * chunk) * chunk;
     if (!h->super_tiles && tiles < 16ull * super) super = 1ull << ceil_log2(per_xcd);
-    if (tiles >= (1ull << 31) || per_xcd * 8ull * (unsigned long long)h->K >= (1ull << 31))
+    if (tiles >= (1ull << 31) || per_xcd * 8ull * (unsigned long long)rows >= (1ull << 31))
         return false;
     ord->tiles = (unsigned)tiles;
     ord->per_xcd = (unsigned)per_xcd;
@@ -417,52 +540,104 @@ bool plan_order(const pso_ps_ctx* h, const ColumnBlock& b, bool vec, unsigned ti
     ord->chunk_log2 = ceil_log2(chunk);
     ord->full = (unsigned)(per_xcd >> ord->super_log2);
     ord->last = (unsigned)(per_xcd - ((unsigned long long)ord->full << ord->super_log2));
-    *grid = per_xcd * 8ull * (unsigned long long)h->K;
+    *grid = per_xcd * 8ull * (unsigned long long)rows;
     return true;
+}
+
+// Tiles per row: with the vector path tiles are aligned to each row's address.
+template <class RowX>
+unsigned long long tiles_per_row(int rows, long long n, bool vec, unsigned tile, RowX row_x) {
+    unsigned long long max_phase = 0;
+    if (vec) {
+        for (int i = 0; i < rows; ++i) {
+            const unsigned long long a = (reinterpret_cast<uintptr_t>(row_x(i)) >> 2) & (tile - 1u);
+            if (a > max_phase) max_phase = a;
+        }
+    }
+    return (max_phase + (unsigned long long)n + tile - 1) / tile;
 }
 
 template <int BLOCK>
 hipError_t launch_update(const pso_ps_ctx* h, const ColumnBlock& b, const MoveParams& m, bool vec,
-                         hipStream_t stream) {
+                         float* gbest_loss, hipStream_t stream) {
     TileOrder ord;
     unsigned long long grid = 0;
-    if (!plan_order(h, b, vec, BLOCK * 4u, &ord, &grid)) return hipErrorInvalidConfiguration;
+    const unsigned long long tiles = tiles_per_row(
+        h->K, b.n, vec, BLOCK * 4u, [&](int i) { return b.x + (long long)i * b.ld; });
+    if (!plan_order(h, h->K, tiles, BLOCK * 4u, &ord, &grid)) return hipErrorInvalidConfiguration;
     if (vec)
         hipLaunchKernelGGL((update_kernel<BLOCK, true>), dim3((unsigned)grid), dim3(BLOCK), 0, stream,
-                           b, h->K, (const Selection*)h->sel, m, ord);
+                           b, h->K, (const Selection*)h->sel, m, ord, gbest_loss);
     else
         hipLaunchKernelGGL((update_kernel<BLOCK, false>), dim3((unsigned)grid), dim3(BLOCK), 0, stream,
-                           b, h->K, (const Selection*)h->sel, m, ord);
+                           b, h->K, (const Selection*)h->sel, m, ord, gbest_loss);
     return hipGetLastError();
 }
 
-// Enqueue the update pass over one dense block (already validated).
-int enqueue_update(pso_ps_ctx* h, const ColumnBlock& b, const MoveParams& m, hipStream_t stream) {
-    if (b.n == 0) return PSO_PS_OK;
-    const bool vec = vector_path_ok(h, b);
-    hipError_t e;
-    switch (h->block_threads ? h->block_threads : kDefaultBlock) {
-        case 64: e = launch_update<64>(h, b, m, vec, stream); break;
-        case 128: e = launch_update<128>(h, b, m, vec, stream); break;
-        case 256: e = launch_update<256>(h, b, m, vec, stream); break;
-        case 512: e = launch_update<512>(h, b, m, vec, stream); break;
-        case 1024: e = launch_update<1024>(h, b, m, vec, stream); break;
-        default: return PSO_PS_EINVAL;
+template <int BLOCK>
+hipError_t launch_update_rows(const pso_ps_ctx* h, const RowTable& tab, const float* gbest,
+                              int row0, int rows, const MoveParams& m, bool vec,
+                              hipStream_t stream) {
+    TileOrder ord;
+    unsigned long long grid = 0;
+    const long long n = (long long)h->D;
+    const unsigned long long tiles =
+        tiles_per_row(rows, n, vec, BLOCK * 4u, [&](int i) { return tab.x[i]; });
+    if (!plan_order(h, rows, tiles, BLOCK * 4u, &ord, &grid)) return hipErrorInvalidConfiguration;
+    if (vec)
+        hipLaunchKernelGGL((update_rows_kernel<BLOCK, true>), dim3((unsigned)grid), dim3(BLOCK), 0,
+                           stream, tab, gbest, n, row0, rows, (const Selection*)h->sel, m, ord);
+    else
+        hipLaunchKernelGGL((update_rows_kernel<BLOCK, false>), dim3((unsigned)grid), dim3(BLOCK), 0,
+                           stream, tab, gbest, n, row0, rows, (const Selection*)h->sel, m, ord);
+    return hipGetLastError();
+}
+
+#define PSO_PS_DISPATCH_BLOCK(h, e, CALL)                              \
+    switch ((h)->block_threads ? (h)->block_threads : kDefaultBlock) { \
+        case 64: e = CALL(64); break;                                  \
+        case 128: e = CALL(128); break;                                \
+        case 256: e = CALL(256); break;                                \
+        case 512: e = CALL(512); break;                                \
+        case 1024: e = CALL(1024); break;                              \
+        default: return PSO_PS_EINVAL;                                 \
     }
+
+// Enqueue the update pass over one dense block (already validated).
+int enqueue_update(pso_ps_ctx* h, const ColumnBlock& b, const MoveParams& m, float* gbest_loss,
+                   hipStream_t stream) {
+    if (b.n == 0) return PSO_PS_OK;
+    const bool vec = block_vector_ok(h, b);
+    hipError_t e;
+#define CALL(B) launch_update<B>(h, b, m, vec, gbest_loss, stream)
+    PSO_PS_DISPATCH_BLOCK(h, e, CALL)
+#undef CALL
     return e == hipSuccess ? PSO_PS_OK : hip_fail(h, e);
 }
 
-// Enqueue selection (if do_select) and the gbest copy of one dense block.
-int enqueue_select_gbest(pso_ps_ctx* h, float* pbest_loss, const float* loss, const ColumnBlock& b,
-                         bool do_select, hipStream_t stream) {
-    constexpr int BLOCK = 256;
-    if (b.n == 0 && !do_select) return PSO_PS_OK;
-    long long blocks = (b.n + 4LL * BLOCK - 1) / (4LL * BLOCK);
+int enqueue_update_rows(pso_ps_ctx* h, const RowTable& tab, const float* gbest, int row0, int rows,
+                        const MoveParams& m, hipStream_t stream) {
+    bool vec = !h->force_generic;
+    for (int i = 0; i < rows && vec; ++i) vec = row_vector_ok(tab.x[i], tab.v[i], tab.pbest[i], 0);
+    hipError_t e;
+#define CALL(B) launch_update_rows<B>(h, tab, gbest, row0, rows, m, vec, stream)
+    PSO_PS_DISPATCH_BLOCK(h, e, CALL)
+#undef CALL
+    return e == hipSuccess ? PSO_PS_OK : hip_fail(h, e);
+}
+
+// Enqueue selection (if do_select) and the gbest copy from `source`.
+template <class Source>
+int enqueue_select_gbest(pso_ps_ctx* h, float* pbest_loss, const float* loss, const Source& source,
+                         float* gbest, long long n, const float* gbest_loss, bool do_select,
+                         hipStream_t stream) {
+    if (n == 0 && !do_select) return PSO_PS_OK;
+    long long blocks = (n + 4LL * kCopyBlock - 1) / (4LL * kCopyBlock);
     if (blocks < 1) blocks = 1;  // selection still has to run
     if (blocks > 0x7fffffffLL) return hip_fail(h, hipErrorInvalidConfiguration);
-    hipLaunchKernelGGL(select_gbest_kernel<BLOCK>, dim3((unsigned)blocks), dim3(BLOCK), 0, stream,
-                       h->K, loss, pbest_loss, h->sel, (const float*)b.x, b.gbest,
-                       b.ld, b.n, do_select ? 1 : 0);
+    hipLaunchKernelGGL((select_gbest_kernel<kCopyBlock, Source>), dim3((unsigned)blocks),
+                       dim3(kCopyBlock), 0, stream, h->K, loss, pbest_loss, h->sel, source, gbest,
+                       n, gbest_loss, do_select ? 1 : 0);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(h, e);
     h->last_stream = stream;
@@ -479,6 +654,23 @@ MoveParams make_params(float w, float c1, float c2, uint64_t seed, uint64_t step
 }
 
 bool is_pow2(int t) { return t > 0 && (t & (t - 1)) == 0; }
+
+// Whole flat stage; gbest_loss == null: best of this stage, else historical gBest.
+int sync_flat(pso_ps_ctx* h, float* x, float* v, float* pbest, float* pbest_loss, const float* loss,
+              float* gbest, float* gbest_loss, const MoveParams& m, hipStream_t stream) {
+    if (!h || !pbest_loss || !loss) return PSO_PS_EINVAL;
+    if (!aligned_to(pbest_loss, 4) || !aligned_to(loss, 4) || !aligned_to(gbest_loss, 4))
+        return PSO_PS_EALIGN;
+    ColumnBlock b{x, v, pbest, gbest, (long long)h->ld, (long long)h->D, 0ull};
+    int rc = check_block(b);
+    if (rc != PSO_PS_OK) return rc;
+    DeviceScope scope(h->device);
+    if (scope.err != hipSuccess) return hip_fail(h, scope.err);
+    rc = enqueue_select_gbest(h, pbest_loss, loss, StackedSource{x, b.ld}, gbest, b.n, gbest_loss,
+                              true, stream);
+    if (rc != PSO_PS_OK) return rc;
+    return enqueue_update(h, b, m, gbest_loss, stream);
+}
 
 }  // namespace
 
@@ -536,8 +728,8 @@ int pso_ps_select(pso_ps_ctx* h, const float* x, float* pbest_loss, const float*
         return PSO_PS_EALIGN;
     DeviceScope scope(h->device);
     if (scope.err != hipSuccess) return hip_fail(h, scope.err);
-    ColumnBlock b{const_cast<float*>(x), nullptr, nullptr, gbest, (long long)h->ld, (long long)h->D, 0ull};
-    return enqueue_select_gbest(h, pbest_loss, loss, b, true, (hipStream_t)hip_stream);
+    return enqueue_select_gbest(h, pbest_loss, loss, StackedSource{x, (long long)h->ld}, gbest,
+                                (long long)h->D, nullptr, true, (hipStream_t)hip_stream);
 }
 
 int pso_ps_update(pso_ps_ctx* h, float* x, float* v, float* pbest, const float* gbest,
@@ -548,7 +740,8 @@ int pso_ps_update(pso_ps_ctx* h, float* x, float* v, float* pbest, const float* 
     if (rc != PSO_PS_OK) return rc;
     DeviceScope scope(h->device);
     if (scope.err != hipSuccess) return hip_fail(h, scope.err);
-    const int rc2 = enqueue_update(h, b, make_params(w, c1, c2, seed, step), (hipStream_t)hip_stream);
+    const int rc2 = enqueue_update(h, b, make_params(w, c1, c2, seed, step), nullptr,
+                                   (hipStream_t)hip_stream);
     if (rc2 == PSO_PS_OK) h->last_stream = (hipStream_t)hip_stream;
     return rc2;
 }
@@ -556,17 +749,16 @@ int pso_ps_update(pso_ps_ctx* h, float* x, float* v, float* pbest, const float* 
 int pso_ps_sync(pso_ps_ctx* h, float* x, float* v, float* pbest, float* pbest_loss,
                 const float* loss, float* gbest, float w, float c1, float c2,
                 uint64_t seed, uint64_t step, void* hip_stream) {
-    if (!h || !pbest_loss || !loss) return PSO_PS_EINVAL;
-    if (!aligned_to(pbest_loss, 4) || !aligned_to(loss, 4)) return PSO_PS_EALIGN;
-    ColumnBlock b{x, v, pbest, gbest, (long long)h->ld, (long long)h->D, 0ull};
-    int rc = check_block(b);
-    if (rc != PSO_PS_OK) return rc;
-    DeviceScope scope(h->device);
-    if (scope.err != hipSuccess) return hip_fail(h, scope.err);
-    const hipStream_t stream = (hipStream_t)hip_stream;
-    rc = enqueue_select_gbest(h, pbest_loss, loss, b, true, stream);
-    if (rc != PSO_PS_OK) return rc;
-    return enqueue_update(h, b, make_params(w, c1, c2, seed, step), stream);
+    return sync_flat(h, x, v, pbest, pbest_loss, loss, gbest, nullptr,
+                     make_params(w, c1, c2, seed, step), (hipStream_t)hip_stream);
+}
+
+int pso_ps_sync_history(pso_ps_ctx* h, float* x, float* v, float* pbest, float* pbest_loss,
+                        const float* loss, float* gbest, float* gbest_loss, float w, float c1,
+                        float c2, uint64_t seed, uint64_t step, void* hip_stream) {
+    if (!gbest_loss) return PSO_PS_EINVAL;
+    return sync_flat(h, x, v, pbest, pbest_loss, loss, gbest, gbest_loss,
+                     make_params(w, c1, c2, seed, step), (hipStream_t)hip_stream);
 }
 
 int pso_ps_sync_segments(pso_ps_ctx* h, float* const* x_seg, float* const* v_seg,
@@ -599,22 +791,98 @@ int pso_ps_sync_segments(pso_ps_ctx* h, float* const* x_seg, float* const* v_seg
     DeviceScope scope(h->device);
     if (scope.err != hipSuccess) return hip_fail(h, scope.err);
     const hipStream_t stream = (hipStream_t)hip_stream;
-    // Selection rides on the first segment's gbest copy; every gbest copy is
-    // enqueued before any update so that all of them see the positions as they
-    // were (segments are separate arrays, so this is only for clarity).
+    // Selection rides on the first segment's gbest copy.
     for (size_t s = 0; s < blocks.size(); ++s) {
-        const int rc = enqueue_select_gbest(h, pbest_loss, loss, blocks[s], s == 0, stream);
+        const ColumnBlock& b = blocks[s];
+        const int rc = enqueue_select_gbest(h, pbest_loss, loss, StackedSource{b.x, b.ld}, b.gbest,
+                                            b.n, nullptr, s == 0, stream);
         if (rc != PSO_PS_OK) return rc;
     }
     const MoveParams m = make_params(w, c1, c2, seed, step);
     for (size_t s = 0; s < blocks.size(); ++s) {
-        const int rc = enqueue_update(h, blocks[s], m, stream);
+        const int rc = enqueue_update(h, blocks[s], m, nullptr, stream);
         if (rc != PSO_PS_OK) return rc;
     }
     return PSO_PS_OK;
 }
 
-int pso_ps_last_selection(pso_ps_ctx* h, int* g_out, uint64_t* improved_mask_out, int mask_words) {
+int pso_ps_sync_rows(pso_ps_ctx* h, float* const* x_rows, float* const* v_rows,
+                     float* const* pbest_rows, float* pbest_loss, const float* loss, float* gbest,
+                     float w, float c1, float c2, uint64_t seed, uint64_t step, void* hip_stream) {
+    if (!h || !x_rows || !v_rows || !pbest_rows || !pbest_loss || !loss || !gbest)
+        return PSO_PS_EINVAL;
+    if (!aligned_to(pbest_loss, 4) || !aligned_to(loss, 4)) return PSO_PS_EALIGN;
+    for (int i = 0; i < h->K; ++i) {
+        const int rc = check_arrays(x_rows[i], v_rows[i], pbest_rows[i], gbest);
+        if (rc != PSO_PS_OK) return rc;
+    }
+    DeviceScope scope(h->device);
+    if (scope.err != hipSuccess) return hip_fail(h, scope.err);
+    const hipStream_t stream = (hipStream_t)hip_stream;
+    const long long n = (long long)h->D;
+    // gbest copies first (each launch carries up to kTableRows row pointers and
+    // copies only if g is among them), then the updates.
+    for (int row0 = 0; row0 < h->K; row0 += kTableRows) {
+        TableSource src;
+        src.row0 = row0;
+        src.rows = (h->K - row0 < kTableRows) ? h->K - row0 : kTableRows;
+        for (int i = 0; i < kTableRows; ++i) src.x[i] = (i < src.rows) ? x_rows[row0 + i] : nullptr;
+        const int rc = enqueue_select_gbest(h, pbest_loss, loss, src, gbest, n, nullptr, row0 == 0,
+                                            stream);
+        if (rc != PSO_PS_OK) return rc;
+    }
+    const MoveParams m = make_params(w, c1, c2, seed, step);
+    for (int row0 = 0; row0 < h->K; row0 += kTableRows) {
+        RowTable tab;
+        const int rows = (h->K - row0 < kTableRows) ? h->K - row0 : kTableRows;
+        for (int i = 0; i < kTableRows; ++i) {
+            tab.x[i] = (i < rows) ? x_rows[row0 + i] : nullptr;
+            tab.v[i] = (i < rows) ? v_rows[row0 + i] : nullptr;
+            tab.pbest[i] = (i < rows) ? pbest_rows[row0 + i] : nullptr;
+        }
+        const int rc = enqueue_update_rows(h, tab, gbest, row0, rows, m, stream);
+        if (rc != PSO_PS_OK) return rc;
+    }
+    return PSO_PS_OK;
+}
+
+int pso_ps_average(pso_ps_ctx* h, float* x, float* mean, void* hip_stream) {
+    if (!h || !x || !mean) return PSO_PS_EINVAL;
+    if (!aligned_to(x, 4) || !aligned_to(mean, 4)) return PSO_PS_EALIGN;
+    DeviceScope scope(h->device);
+    if (scope.err != hipSuccess) return hip_fail(h, scope.err);
+    const long long n = (long long)h->D;
+    const long long blocks = (n + 4LL * kCopyBlock - 1) / (4LL * kCopyBlock);
+    if (blocks > 0x7fffffffLL) return hip_fail(h, hipErrorInvalidConfiguration);
+    hipLaunchKernelGGL(average_kernel<kCopyBlock>, dim3((unsigned)blocks), dim3(kCopyBlock), 0,
+                       (hipStream_t)hip_stream, x, mean, (long long)h->ld, n, h->K);
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? PSO_PS_OK : hip_fail(h, e);
+}
+
+float pso_ps_inertia(int64_t t, int64_t t_max, float m_max, float m_min) {
+    const double span = (double)m_max - (double)m_min;
+    return (float)((double)m_max - ((double)t * span) / (double)t_max);
+}
+
+int pso_ps_schedule(int64_t t, int64_t iteration_size, int64_t epoch_size, int64_t step,
+                    float m_max, float m_min, float c1, float c2,
+                    int* is_stage, float* w, float* c1_eff, float* c2_eff) {
+    if (!is_stage || !w || !c1_eff || !c2_eff) return PSO_PS_EINVAL;
+    if (t < 1 || iteration_size < 1 || epoch_size < 1 || step < 1) return PSO_PS_EINVAL;
+    if (epoch_size > INT64_MAX / iteration_size) return PSO_PS_EINVAL;
+    const int64_t last = epoch_size * iteration_size;  // Max_t of Algorithm 1
+    if (t > last) return PSO_PS_EINVAL;
+    const float lambda = (float)((t - 1) / iteration_size + 1);
+    *is_stage = (t < last && t % step == 0) ? 1 : 0;
+    *w = pso_ps_inertia(t, last, m_max, m_min);
+    *c1_eff = c1 / lambda;
+    *c2_eff = c2 / lambda;
+    return PSO_PS_OK;
+}
+
+int pso_ps_last_selection(pso_ps_ctx* h, int* g_out, uint64_t* improved_mask_out, int mask_words,
+                          int* replaced_out) {
     if (!h || !h->have_selection) return PSO_PS_EINVAL;
     if (improved_mask_out && mask_words < h->mask_words) return PSO_PS_EINVAL;
     DeviceScope scope(h->device);
@@ -631,6 +899,7 @@ int pso_ps_last_selection(pso_ps_ctx* h, int* g_out, uint64_t* improved_mask_out
     if (e != hipSuccess) return hip_fail(h, e);
     const Selection* s = reinterpret_cast<const Selection*>(host.data());
     if (g_out) *g_out = s->g;
+    if (replaced_out) *replaced_out = s->replaced;
     if (improved_mask_out)
         for (int j = 0; j < h->mask_words; ++j) improved_mask_out[j] = s->improved[j];
     return PSO_PS_OK;

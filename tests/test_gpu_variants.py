@@ -1,0 +1,142 @@
+"""GPU parity of the companions of the stage: historical gBest, row-pointer
+mode, parameter averaging, and a run driven by the paper's schedule
+(Table II, Eq. (5), lambda, step = 10).  Same bar as the main parity tests."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2009_03816_amd as pso
+from paper_2009_03816_amd import workloads as wl
+
+import gpu_harness as gh
+
+pytestmark = pytest.mark.gpu
+F32 = np.float32
+
+
+def compare_state(dev, host, what):
+    """dev / host: (x, v, pbest, pbest_loss, gbest) as device tensors / numpy arrays."""
+    gh.assert_bits_equal(dev[3].cpu().numpy(), host[3], what + ": pbest_loss")
+    gh.assert_bits_equal(dev[4].cpu().numpy(), host[4], what + ": gbest")
+    gh.assert_bits_equal(dev[2].cpu().numpy(), host[2], what + ": pbest")
+    gh.assert_close(dev[0].cpu().numpy(), host[0], what + ": x")
+    gh.assert_close(dev[1].cpu().numpy(), host[1], what + ": v")
+
+
+@pytest.mark.parametrize("K,D,steps", [(6, 10_242, 14), (8, 1_000_002, 6)])
+def test_history_trajectory(oracle, K, D, steps):
+    print(f"[case] historical gBest K={K} D={D}", flush=True)
+    sw = wl.small_swarm(K, D, seed=31, steps=steps)
+    losses = sw.losses.copy()
+    losses[3] = losses[:3].min() + F32(0.5)          # a stage that cannot replace
+    if steps > 8:
+        losses[8] = 2.0; losses[8, 2] = losses[:8].min()   # ties the best so far: kept
+        losses[9] = np.nan
+    host = [sw.x.copy(), sw.v.copy(), sw.pbest.copy(), sw.pbest_loss.copy(), np.full(D, 3.0, F32)]
+    hgl = np.array([np.inf], F32)
+    dev = [gh.to_dev(a) for a in host]
+    dgl = gh.to_dev(hgl)
+    h = pso.pso_ps_create(K, D)
+    kept = 0
+    try:
+        for s in range(steps):
+            pso.pso_ps_sync_history(h, dev[0], dev[1], dev[2], dev[3], gh.to_dev(losses[s]), dev[4],
+                                    dgl, 0.7, 1.2, 1.3, 31, s)
+            g, improved, rep = oracle.sync(host[0], host[1], host[2], host[3], losses[s], host[4],
+                                           F32(0.7), F32(1.2), F32(1.3), 31, s, gbest_loss=hgl)
+            gg, gi, grep = pso.pso_ps_last_selection(h, K, with_replaced=True)
+            what = f"history K={K} D={D} step {s}"
+            assert (gg, gi, grep) == (g, [bool(t) for t in improved], rep), what
+            gh.assert_bits_equal(dgl.cpu().numpy(), hgl, what + ": gbest_loss")
+            compare_state(dev, host, what)
+            kept += not rep
+        assert 0 < kept < steps
+    finally:
+        torch.cuda.synchronize()
+        pso.pso_ps_destroy(h)
+
+
+@pytest.mark.parametrize("K,D,offsets", [
+    (5, 20_000, [0, 0, 0, 0, 0]),              # separately allocated rows, all vector path
+    (5, 20_002, [0, 2, 0, 2, 2]),              # some rows 8-byte aligned only
+    (4, 9_001, [0, 1, 0, 0]),                  # a 4-byte aligned row: whole launch element-wise
+    (40, 3_000, [0] * 40),                     # two launches of row pointers (32 + 8)
+    (33, 1_030, [2 * (i % 2) for i in range(33)]),
+])
+def test_row_pointer_mode(oracle, K, D, offsets):
+    print(f"[case] row pointers K={K} D={D} offsets={offsets[:6]}", flush=True)
+    sw = wl.small_swarm(K, D, seed=41 + K, steps=3)
+    if K >= 33:
+        sw.losses[1, K - 1] = 0.01             # g in the second group of rows
+    host = [sw.x.copy(), sw.v.copy(), sw.pbest.copy(), sw.pbest_loss.copy(), np.zeros(D, F32)]
+    rows = [[gh.to_dev(a[i], offsets[i]) for i in range(K)] for a in (sw.x, sw.v, sw.pbest)]
+    dpl, dg = gh.to_dev(sw.pbest_loss), gh.to_dev(np.zeros(D, F32))
+    h = pso.pso_ps_create(K, D)
+    try:
+        for s in range(3):
+            pso.pso_ps_sync_rows(h, rows[0], rows[1], rows[2], dpl, gh.to_dev(sw.losses[s]), dg,
+                                 0.7, 1.5, 1.5, 7, s)
+            g, improved = oracle.sync(host[0], host[1], host[2], host[3], sw.losses[s], host[4],
+                                      F32(0.7), F32(1.5), F32(1.5), 7, s)
+            gg, gi = pso.pso_ps_last_selection(h, K)
+            assert (gg, gi) == (g, [bool(t) for t in improved])
+            stack = lambda parts: torch.stack(parts)
+            dev = [stack(rows[0]), stack(rows[1]), stack(rows[2]), dpl, dg]
+            compare_state(dev, host, f"rows K={K} D={D} step {s}")
+    finally:
+        torch.cuda.synchronize()
+        pso.pso_ps_destroy(h)
+
+
+@pytest.mark.parametrize("K,D,ld,offset", [(1, 5, 5, 0), (2, 1_000, 1_000, 0), (5, 4_099, 4_099, 0),
+                                           (7, 70_001, 70_004, 1), (32, 33_333, 33_336, 0),
+                                           (16, 272_474, 272_474, 2)])
+def test_parameter_averaging(oracle, K, D, ld, offset):
+    print(f"[case] averaging K={K} D={D} ld={ld} offset={offset}", flush=True)
+    sw = wl.small_swarm(K, D, seed=51 + K, ld=ld, steps=1)
+    sw.x[:, D:] = 7.0
+    hx, hmean = sw.x.copy(), np.zeros(D, F32)
+    dx, dmean = gh.to_dev(sw.x, offset), gh.to_dev(np.zeros(D, F32), offset)
+    h = pso.pso_ps_create(K, D, ld)
+    try:
+        pso.pso_ps_average(h, dx, dmean)
+        oracle.average(hx[:, :D], hmean)
+        gh.assert_bits_equal(dmean.cpu().numpy(), hmean, "mean")
+        gh.assert_bits_equal(dx.cpu().numpy(), hx, "rows after averaging")
+    finally:
+        torch.cuda.synchronize()
+        pso.pso_ps_destroy(h)
+
+
+def test_run_with_the_papers_schedule(oracle):
+    """Table II constants, inertia by Eq. (5), lambda = epoch number, a stage
+    every 10th iteration: the library's schedule drives the library, the
+    oracle's schedule drives the oracle."""
+    K, D = 16, 61_706
+    it, ep, step = 234, 2, 10
+    print(f"[case] paper schedule K={K} D={D}, {it * ep} iterations", flush=True)
+    consts = (F32(0.9), F32(0.3), F32(0.2), F32(0.9))
+    sw = wl.small_swarm(K, D, seed=61, steps=it * ep // step + 1, x_sigma=0.1, v_sigma=0.01)
+    host = [sw.x.copy(), sw.v.copy(), sw.pbest.copy(), sw.pbest_loss.copy(), np.zeros(D, F32)]
+    dev = [gh.to_dev(a) for a in host]
+    h = pso.pso_ps_create(K, D)
+    stages = 0
+    try:
+        for t in range(1, it * ep + 1):
+            is_stage, w, a1, a2 = pso.pso_ps_schedule(t, it, ep, step, *consts)
+            o_stage, ow, oa1, oa2 = oracle.schedule(t, it, ep, step, *consts)
+            assert is_stage == o_stage
+            if not is_stage:
+                continue                       # (local training would run here)
+            loss = sw.losses[stages]
+            pso.pso_ps_sync(h, dev[0], dev[1], dev[2], dev[3], gh.to_dev(loss), dev[4],
+                            w, a1, a2, 61, stages)
+            oracle.sync(host[0], host[1], host[2], host[3], loss, host[4], ow, oa1, oa2, 61, stages)
+            stages += 1
+            if stages % 6 == 0 or stages < 3:
+                compare_state(dev, host, f"paper schedule stage {stages} (t={t})")
+        assert stages == (it * ep - 1) // step
+        compare_state(dev, host, "paper schedule, final state")
+    finally:
+        torch.cuda.synchronize()
+        pso.pso_ps_destroy(h)
