@@ -84,6 +84,9 @@ def main() -> int:
     ap.add_argument("--block", type=int, default=0, help="threads per workgroup (0 = default)")
     ap.add_argument("--super-tiles", type=int, default=0)
     ap.add_argument("--chunk-tiles", type=int, default=0)
+    ap.add_argument("--variant", default="sync", choices=["sync", "history", "rows", "average"],
+                    help="sync: the stage (default, the headline); history: historical gBest; "
+                         "rows: K separate per-worker arrays; average: parameter averaging")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch one plain device copy of 1 GiB (counter calibration)")
@@ -107,12 +110,19 @@ def main() -> int:
     total = args.warmup + args.steps
 
     sw = wl.make_swarm(cfg, steps=total)
-    dx = torch.from_numpy(sw.x).to(dev)
-    dv = torch.from_numpy(sw.v).to(dev)
-    dp = dx.clone()
+    if args.variant == "rows":                           # K separately allocated arrays
+        xr = [torch.from_numpy(sw.x[i]).to(dev) for i in range(K)]
+        vr = [torch.from_numpy(sw.v[i]).to(dev) for i in range(K)]
+        pr = [t.clone() for t in xr]
+        dx = xr[0]
+    else:
+        dx = torch.from_numpy(sw.x).to(dev)
+        dv = torch.from_numpy(sw.v).to(dev)
+        dp = dx.clone()
     dpl = torch.from_numpy(sw.pbest_loss).to(dev)
     dloss = torch.from_numpy(sw.losses).to(dev)          # [total, K], resident
     dg = torch.zeros(D, dtype=torch.float32, device=dev)
+    dgl = torch.full((1,), float("inf"), dtype=torch.float32, device=dev)
     w_tab, c1, c2 = [float(t) for t in sw.w], float(sw.c1), float(sw.c2)
     del sw
 
@@ -122,10 +132,22 @@ def main() -> int:
     stream = torch.cuda.current_stream()
 
     def stage(s, ev=None):
-        pso.pso_ps_select(h, dx, dpl, dloss[s], dg, stream)
+        # events bracket the dominant kernel where the entry points allow it,
+        # else the whole call (history, rows: selection + update)
+        if args.variant == "sync":
+            pso.pso_ps_select(h, dx, dpl, dloss[s], dg, stream)
         if ev:
             ev[0].record(stream)
-        pso.pso_ps_update(h, dx, dv, dp, dg, w_tab[s], c1, c2, cfg.seed, s, stream)
+        if args.variant == "sync":
+            pso.pso_ps_update(h, dx, dv, dp, dg, w_tab[s], c1, c2, cfg.seed, s, stream)
+        elif args.variant == "history":
+            pso.pso_ps_sync_history(h, dx, dv, dp, dpl, dloss[s], dg, dgl, w_tab[s], c1, c2,
+                                    cfg.seed, s, stream)
+        elif args.variant == "rows":
+            pso.pso_ps_sync_rows(h, xr, vr, pr, dpl, dloss[s], dg, w_tab[s], c1, c2, cfg.seed, s,
+                                 stream)
+        else:
+            pso.pso_ps_average(h, dx, dg, stream)
         if ev:
             ev[1].record(stream)
 
@@ -142,7 +164,16 @@ def main() -> int:
 
     kernel_ms = [a.elapsed_time(b) for a, b in events]
     avg_ms = sum(kernel_ms) / len(kernel_ms)
-    algo_bytes = 4.0 * D * (5 * K + 1)                   # per update launch
+    if args.variant == "average":
+        algo_bytes = 4.0 * D * (2 * K + 1)               # read K rows, write K rows and the mean
+        kernel = "mean_kernel + broadcast_kernel"
+    elif args.variant == "sync":
+        algo_bytes = 4.0 * D * (5 * K + 1)               # per update launch
+        kernel = "update_kernel"
+    else:
+        algo_bytes = 4.0 * D * (5 * K + 3)               # whole call: + read x_g, write gbest
+        kernel = "select_gbest_kernel + " + ("update_rows_kernel" if args.variant == "rows"
+                                             else "update_kernel")
     achieved = algo_bytes / (avg_ms * 1e-3) / 1e9
     assert bool(torch.isfinite(dx).all()), "state went non-finite"
 
@@ -152,23 +183,26 @@ def main() -> int:
         dst.copy_(src)
         torch.cuda.synchronize()
 
-    traffic = MEASURED_TRAFFIC.get((cfg.name, kernel_source_hash()))
+    traffic = MEASURED_TRAFFIC.get((cfg.name, kernel_source_hash())) if args.variant == "sync" \
+        else None
     out = {
-        "metric": "PSO sync particle-params/s", "value": K * D * args.steps / elapsed,
+        "metric": "PSO sync particle-params/s" if args.variant != "average"
+        else "parameter-averaging particle-params/s", "value": K * D * args.steps / elapsed,
         "unit": "particle-params/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: K={K} particles x D={D} fp32 parameters, "
-                               f"w={cfg.w[0]}, c1={cfg.c1}, c2={cfg.c2}", "K": K, "D": D},
-        "roofline": {"bound": "hbm", "kernel": "update_kernel", "achieved": achieved,
+                               f"w={cfg.w[0]}, c1={cfg.c1}, c2={cfg.c2}", "K": K, "D": D,
+                   "variant": args.variant},
+        "roofline": {"bound": "hbm", "kernel": kernel, "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic, "algorithmic_bytes_per_launch": algo_bytes,
                      "kernel_ms_avg": avg_ms, "kernel_ms_min": min(kernel_ms)},
     }
     torch.cuda.synchronize()
     pso.pso_ps_destroy(h)
-    del dx, dv, dp, dg
-    if not args.no_cpu_baseline:
+    del dx, dg
+    if not args.no_cpu_baseline and args.variant == "sync":
         out["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(out))
     return 0

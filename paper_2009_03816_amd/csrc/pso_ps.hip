@@ -396,12 +396,13 @@ __global__ __launch_bounds__(BLOCK) void select_gbest_kernel(int K, const float*
     }
 }
 
-// Parameter averaging (Section II-B, step 5) on the stacked layout: one thread
-// owns four columns, sums the K rows in order, divides by K, and writes the
-// mean back to every row and to `mean`.  8 K + 4 bytes per column.
+// Parameter averaging (Section II-B, step 5) on the stacked layout, first half:
+// one thread owns four columns, sums the K rows in order and divides by K.
+// Reading K rows at one column is tolerant of the rows' different alignments.
 template <int BLOCK>
-__global__ __launch_bounds__(BLOCK) void average_kernel(float* x, float* __restrict__ mean,
-                                                        long long ld, long long n, int K) {
+__global__ __launch_bounds__(BLOCK) void mean_kernel(const float* __restrict__ x,
+                                                     float* __restrict__ mean, long long ld,
+                                                     long long n, int K) {
     const long long c = ((long long)blockIdx.x * BLOCK + threadIdx.x) * 4;
     if (c >= n) return;
     const float kf = (float)K;
@@ -410,18 +411,38 @@ __global__ __launch_bounds__(BLOCK) void average_kernel(float* x, float* __restr
         for (int k = 1; k < K; ++k)
             sum = sum + __builtin_nontemporal_load(
                             reinterpret_cast<const f32x4_a4*>(x + (long long)k * ld + c));
-        const f32x4 avg = {sum.x / kf, sum.y / kf, sum.z / kf, sum.w / kf};
-        *reinterpret_cast<f32x4_a4*>(mean + c) = avg;
-        for (int k = 0; k < K; ++k)
-            __builtin_nontemporal_store(avg, reinterpret_cast<f32x4_a4*>(x + (long long)k * ld + c));
+        *reinterpret_cast<f32x4_a4*>(mean + c) =
+            f32x4{sum.x / kf, sum.y / kf, sum.z / kf, sum.w / kf};
     } else {
         for (long long e = c; e < n; ++e) {
             float sum = x[e];
             for (int k = 1; k < K; ++k) sum = sum + x[(long long)k * ld + e];
-            const float avg = sum / kf;
-            mean[e] = avg;
-            for (int k = 0; k < K; ++k) x[(long long)k * ld + e] = avg;
+            mean[e] = sum / kf;
         }
+    }
+}
+
+// Second half: every row becomes the mean.  Writes want whole 128-byte lines,
+// so this is one row x one address-aligned tile per workgroup, in the same
+// order as the update pass; the mean tile is re-read through the caches.
+template <int BLOCK, bool VEC>
+__global__ __launch_bounds__(BLOCK) void broadcast_kernel(float* x, const float* __restrict__ mean,
+                                                          long long ld, long long n, int K,
+                                                          TileOrder ord) {
+    constexpr unsigned TILE = BLOCK * 4;
+    unsigned i, tile;
+    if (!decode_workgroup(ord, (unsigned)K, &i, &tile)) return;
+    float* row = x + (long long)i * ld;
+    long long phase = 0;
+    if (VEC) phase = (long long)((reinterpret_cast<uintptr_t>(row) >> 2) & (TILE - 1u));
+    const long long c = (long long)tile * TILE - phase + 4 * (long long)threadIdx.x;
+    if (c + 4 <= 0 || c >= n) return;
+    if (VEC && c >= 0 && c + 4 <= n) {
+        const f32x4 m = *reinterpret_cast<const f32x4_a4*>(mean + c);
+        __builtin_nontemporal_store(m, reinterpret_cast<f32x4*>(row + c));
+    } else {
+        for (int e = 0; e < 4; ++e)
+            if (c + e >= 0 && c + e < n) row[c + e] = mean[c + e];
     }
 }
 
@@ -851,12 +872,32 @@ int pso_ps_average(pso_ps_ctx* h, float* x, float* mean, void* hip_stream) {
     if (!aligned_to(x, 4) || !aligned_to(mean, 4)) return PSO_PS_EALIGN;
     DeviceScope scope(h->device);
     if (scope.err != hipSuccess) return hip_fail(h, scope.err);
+    const hipStream_t stream = (hipStream_t)hip_stream;
     const long long n = (long long)h->D;
+    const long long ld = (long long)h->ld;
     const long long blocks = (n + 4LL * kCopyBlock - 1) / (4LL * kCopyBlock);
     if (blocks > 0x7fffffffLL) return hip_fail(h, hipErrorInvalidConfiguration);
-    hipLaunchKernelGGL(average_kernel<kCopyBlock>, dim3((unsigned)blocks), dim3(kCopyBlock), 0,
-                       (hipStream_t)hip_stream, x, mean, (long long)h->ld, n, h->K);
-    const hipError_t e = hipGetLastError();
+    hipLaunchKernelGGL(mean_kernel<kCopyBlock>, dim3((unsigned)blocks), dim3(kCopyBlock), 0, stream,
+                       (const float*)x, mean, ld, n, h->K);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(h, e);
+    // Tiles are aligned to each row's own address, so any 4-byte aligned row
+    // can take the 128-bit stores.
+    const bool vec = !h->force_generic;
+    constexpr int BLOCK = kDefaultBlock;
+    TileOrder ord;
+    unsigned long long grid = 0;
+    const unsigned long long tiles =
+        tiles_per_row(h->K, n, vec, BLOCK * 4u, [&](int i) { return x + (long long)i * ld; });
+    if (!plan_order(h, h->K, tiles, BLOCK * 4u, &ord, &grid))
+        return hip_fail(h, hipErrorInvalidConfiguration);
+    if (vec)
+        hipLaunchKernelGGL((broadcast_kernel<BLOCK, true>), dim3((unsigned)grid), dim3(BLOCK), 0,
+                           stream, x, (const float*)mean, ld, n, h->K, ord);
+    else
+        hipLaunchKernelGGL((broadcast_kernel<BLOCK, false>), dim3((unsigned)grid), dim3(BLOCK), 0,
+                           stream, x, (const float*)mean, ld, n, h->K, ord);
+    e = hipGetLastError();
     return e == hipSuccess ? PSO_PS_OK : hip_fail(h, e);
 }
 
