@@ -111,6 +111,30 @@ struct TileOrder {
     unsigned last;        // entries in the last, shorter super-chunk (0 if none)
 };
 
+// Ragged mode: up to kTableSegs dense [K, n] segments share one launch.  Each
+// keeps its own workgroup order; its workgroups are first_update_wg .. (a
+// multiple of 8, so that wg & 7 is still the XCD) in the update launch and
+// first_copy_wg .. in the gbest copy launch.
+constexpr int kTableSegs = 16;
+struct SegEntry {
+    float* x;
+    float* v;
+    float* pbest;
+    float* gbest;
+    long long n;
+    unsigned long long d0;
+    TileOrder ord;
+    unsigned first_update_wg;
+    unsigned first_copy_wg;
+    int vec;
+    int reserved;
+};
+struct SegTable {
+    SegEntry seg[kTableSegs];
+    int count;
+};
+
+
 // ---------------------------------------------------------------------------
 // Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11): ten rounds of two
 // 32x32->64 multiplications and a word permutation with key injection; the
@@ -217,12 +241,13 @@ __device__ __forceinline__ void move_quad(const RowPtrs& r, const float* __restr
     if (improved) __builtin_nontemporal_store(x_old, reinterpret_cast<f32x4*>(pp));
 }
 
-// Which (row, tile) does this workgroup handle?  `rows` rows share the order.
-// Returns false for the padding workgroups at the end of an XCD's list.
-__device__ __forceinline__ bool decode_workgroup(const TileOrder& ord, unsigned rows,
+// Which (row, tile) does workgroup `wg` of a launch (or of a segment's share of
+// a launch, which starts at a multiple of 8) handle?  `rows` rows share the
+// order.  Returns false for the padding workgroups at the end of an XCD's list.
+__device__ __forceinline__ bool decode_workgroup(const TileOrder& ord, unsigned rows, unsigned wg,
                                                  unsigned* row, unsigned* tile) {
-    const unsigned xcd = blockIdx.x & 7u;
-    const unsigned j = blockIdx.x >> 3;
+    const unsigned xcd = wg & 7u;
+    const unsigned j = wg >> 3;
     const unsigned super = 1u << ord.super_log2;
     const unsigned full_span = (ord.full << ord.super_log2) * rows;
     unsigned i, u;
@@ -277,7 +302,7 @@ __global__ __launch_bounds__(BLOCK) void update_kernel(ColumnBlock b, int K,
                                                        float* gbest_loss) {
     if (gbest_loss && blockIdx.x == 0 && threadIdx.x == 0) *gbest_loss = sel->gbest_loss;
     unsigned i, tile;
-    if (!decode_workgroup(ord, (unsigned)K, &i, &tile)) return;
+    if (!decode_workgroup(ord, (unsigned)K, blockIdx.x, &i, &tile)) return;
     const long long row = (long long)i * b.ld;
     const RowPtrs r{b.x + row, b.v + row, b.pbest + row};
     update_tile<BLOCK, VEC>(r, b.gbest, b.n, b.d0, i, tile, is_improved(sel, (int)i), m);
@@ -290,10 +315,41 @@ __global__ __launch_bounds__(BLOCK) void update_rows_kernel(RowTable tab, const 
                                                             const Selection* __restrict__ sel,
                                                             MoveParams m, TileOrder ord) {
     unsigned i, tile;
-    if (!decode_workgroup(ord, (unsigned)rows, &i, &tile)) return;
+    if (!decode_workgroup(ord, (unsigned)rows, blockIdx.x, &i, &tile)) return;
     const RowPtrs r{tab.x[i], tab.v[i], tab.pbest[i]};
     const unsigned particle = (unsigned)row0 + i;
     update_tile<BLOCK, VEC>(r, gbest, n, 0ull, particle, tile, is_improved(sel, (int)particle), m);
+}
+
+// The entry of the segment that workgroup `wg` belongs to (entries are sorted
+// by their first workgroup).  Written as a chain of uniform selects over the
+// by-value table, so that the table stays in scalar registers.
+template <bool COPY>
+__device__ __forceinline__ SegEntry segment_of(const SegTable& tab, unsigned wg) {
+    SegEntry e = tab.seg[0];
+#pragma unroll
+    for (int s = 1; s < kTableSegs; ++s) {
+        const unsigned first = COPY ? tab.seg[s].first_copy_wg : tab.seg[s].first_update_wg;
+        if (s < tab.count && wg >= first) e = tab.seg[s];
+    }
+    return e;
+}
+
+// Update pass over up to kTableSegs ragged segments in one launch.
+template <int BLOCK>
+__global__ __launch_bounds__(BLOCK) void update_segments_kernel(SegTable tab, int K,
+                                                                const Selection* __restrict__ sel,
+                                                                MoveParams m) {
+    const SegEntry e = segment_of<false>(tab, blockIdx.x);
+    unsigned i, tile;
+    if (!decode_workgroup(e.ord, (unsigned)K, blockIdx.x - e.first_update_wg, &i, &tile)) return;
+    const long long row = (long long)i * e.n;  // segments are dense: row stride = n
+    const RowPtrs r{e.x + row, e.v + row, e.pbest + row};
+    const bool improved = is_improved(sel, (int)i);
+    if (e.vec)
+        update_tile<BLOCK, true>(r, e.gbest, e.n, e.d0, i, tile, improved, m);
+    else
+        update_tile<BLOCK, false>(r, e.gbest, e.n, e.d0, i, tile, improved, m);
 }
 
 // Where the gbest copy finds row g: in a stacked array, or among the rows that
@@ -396,6 +452,35 @@ __global__ __launch_bounds__(BLOCK) void select_gbest_kernel(int K, const float*
     }
 }
 
+// Selection (if do_select) and the gbest copies of up to kTableSegs segments.
+template <int BLOCK>
+__global__ __launch_bounds__(BLOCK) void select_gbest_segments_kernel(
+    int K, const float* __restrict__ loss, float* pbest_loss, Selection* sel, SegTable tab,
+    int do_select) {
+    int g;
+    if (do_select) {
+        const bool publisher = blockIdx.x == 0 && threadIdx.x < 64;
+        float best;
+        wave_argmin(K, loss, pbest_loss, sel, publisher, &best, &g);
+        if (publisher && (threadIdx.x & 63) == 0) {
+            sel->g = g;
+            sel->replaced = 1;
+            sel->gbest_loss = best;
+        }
+    } else {
+        g = sel->g;
+    }
+    const SegEntry e = segment_of<true>(tab, blockIdx.x);
+    const long long c = ((long long)(blockIdx.x - e.first_copy_wg) * BLOCK + threadIdx.x) * 4;
+    if (c >= e.n) return;
+    const float* src = e.x + (long long)g * e.n;
+    if (c + 4 <= e.n) {
+        *reinterpret_cast<f32x4_a4*>(e.gbest + c) = *reinterpret_cast<const f32x4_a4*>(src + c);
+    } else {
+        for (long long k = c; k < e.n; ++k) e.gbest[k] = src[k];
+    }
+}
+
 // Parameter averaging (Section II-B, step 5) on the stacked layout, first half:
 // one thread owns four columns, sums the K rows in order and divides by K.
 // Reading K rows at one column is tolerant of the rows' different alignments.
@@ -431,7 +516,7 @@ __global__ __launch_bounds__(BLOCK) void broadcast_kernel(float* x, const float*
                                                           TileOrder ord) {
     constexpr unsigned TILE = BLOCK * 4;
     unsigned i, tile;
-    if (!decode_workgroup(ord, (unsigned)K, &i, &tile)) return;
+    if (!decode_workgroup(ord, (unsigned)K, blockIdx.x, &i, &tile)) return;
     float* row = x + (long long)i * ld;
     long long phase = 0;
     if (VEC) phase = (long long)((reinterpret_cast<uintptr_t>(row) >> 2) & (TILE - 1u));
@@ -793,6 +878,7 @@ int pso_ps_sync_segments(pso_ps_ctx* h, float* const* x_seg, float* const* v_seg
     const int n_seg = (int)h->seg_sizes.size();
     // Validate every segment before anything is enqueued.
     std::vector<ColumnBlock> blocks;
+    std::vector<unsigned> update_totals, copy_totals;
     try {
         blocks.reserve((size_t)n_seg);
     } catch (...) {
@@ -812,17 +898,68 @@ int pso_ps_sync_segments(pso_ps_ctx* h, float* const* x_seg, float* const* v_seg
     DeviceScope scope(h->device);
     if (scope.err != hipSuccess) return hip_fail(h, scope.err);
     const hipStream_t stream = (hipStream_t)hip_stream;
-    // Selection rides on the first segment's gbest copy.
-    for (size_t s = 0; s < blocks.size(); ++s) {
-        const ColumnBlock& b = blocks[s];
-        const int rc = enqueue_select_gbest(h, pbest_loss, loss, StackedSource{b.x, b.ld}, b.gbest,
-                                            b.n, nullptr, s == 0, stream);
-        if (rc != PSO_PS_OK) return rc;
-    }
     const MoveParams m = make_params(w, c1, c2, seed, step);
-    for (size_t s = 0; s < blocks.size(); ++s) {
-        const int rc = enqueue_update(h, blocks[s], m, nullptr, stream);
-        if (rc != PSO_PS_OK) return rc;
+    const int block = h->block_threads ? h->block_threads : kDefaultBlock;
+    // Up to kTableSegs segments per launch; the selection rides on the first
+    // gbest-copy launch.  All copies are enqueued before the first update.
+    std::vector<SegTable> tables;
+    try {
+        tables.reserve((blocks.size() + kTableSegs - 1) / kTableSegs);
+        for (size_t first = 0; first < blocks.size(); first += kTableSegs) {
+            SegTable tab;
+            tab.count = (int)((blocks.size() - first < (size_t)kTableSegs) ? blocks.size() - first
+                                                                          : (size_t)kTableSegs);
+            unsigned long long update_wg = 0, copy_wg = 0;
+            for (int s = 0; s < kTableSegs; ++s) {
+                SegEntry& e = tab.seg[s];
+                if (s >= tab.count) {
+                    e = tab.seg[tab.count - 1];
+                    continue;
+                }
+                const ColumnBlock& b = blocks[first + s];
+                e.x = b.x; e.v = b.v; e.pbest = b.pbest; e.gbest = b.gbest;
+                e.n = b.n; e.d0 = b.d0; e.reserved = 0;
+                e.vec = block_vector_ok(h, b) ? 1 : 0;
+                const unsigned tile = (unsigned)block * 4u;
+                const unsigned long long tiles = tiles_per_row(
+                    h->K, b.n, e.vec != 0, tile, [&](int i) { return b.x + (long long)i * b.ld; });
+                unsigned long long grid = 0;
+                if (!plan_order(h, h->K, tiles, tile, &e.ord, &grid))
+                    return hip_fail(h, hipErrorInvalidConfiguration);
+                e.first_update_wg = (unsigned)update_wg;
+                e.first_copy_wg = (unsigned)copy_wg;
+                update_wg += grid;
+                copy_wg += (unsigned long long)((b.n + 4LL * kCopyBlock - 1) / (4LL * kCopyBlock));
+                if (update_wg >= (1ull << 31) || copy_wg >= (1ull << 31))
+                    return hip_fail(h, hipErrorInvalidConfiguration);
+            }
+            tables.push_back(tab);
+            update_totals.push_back((unsigned)update_wg);
+            copy_totals.push_back((unsigned)copy_wg);
+        }
+    } catch (...) {
+        return PSO_PS_ENOMEM;
+    }
+    for (size_t t = 0; t < tables.size(); ++t) {
+        hipLaunchKernelGGL(select_gbest_segments_kernel<kCopyBlock>, dim3(copy_totals[t]),
+                           dim3(kCopyBlock), 0, stream, h->K, loss, pbest_loss, h->sel, tables[t],
+                           t == 0 ? 1 : 0);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail(h, e);
+    }
+    h->last_stream = stream;
+    h->have_selection = true;
+    for (size_t t = 0; t < tables.size(); ++t) {
+        switch (block) {
+            case 64: hipLaunchKernelGGL(update_segments_kernel<64>, dim3(update_totals[t]), dim3(64), 0, stream, tables[t], h->K, (const Selection*)h->sel, m); break;
+            case 128: hipLaunchKernelGGL(update_segments_kernel<128>, dim3(update_totals[t]), dim3(128), 0, stream, tables[t], h->K, (const Selection*)h->sel, m); break;
+            case 256: hipLaunchKernelGGL(update_segments_kernel<256>, dim3(update_totals[t]), dim3(256), 0, stream, tables[t], h->K, (const Selection*)h->sel, m); break;
+            case 512: hipLaunchKernelGGL(update_segments_kernel<512>, dim3(update_totals[t]), dim3(512), 0, stream, tables[t], h->K, (const Selection*)h->sel, m); break;
+            case 1024: hipLaunchKernelGGL(update_segments_kernel<1024>, dim3(update_totals[t]), dim3(1024), 0, stream, tables[t], h->K, (const Selection*)h->sel, m); break;
+            default: return PSO_PS_EINVAL;
+        }
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail(h, e);
     }
     return PSO_PS_OK;
 }

@@ -71,10 +71,14 @@ def test_lenet5_segments_match_flat_and_oracle(oracle):
         pso.pso_ps_destroy(h)
 
 
-def test_odd_and_empty_segments(oracle):
+@pytest.mark.parametrize("sizes", [
+    [5, 0, 1, 1024, 3, 4097, 2, 7],
+    # more segments than one launch carries, ResNet-like: many small tensors and a few large ones
+    [64, 64, 1728, 64, 64] * 7 + [0, 36_864, 1, 73_728, 128, 128, 10],
+])
+def test_odd_and_empty_segments(oracle, sizes):
     """Segment sizes that are odd (a Philox pair straddles two segments),
-    one, and zero."""
-    sizes = [5, 0, 1, 1024, 3, 4097, 2, 7]
+    one, and zero; several launches' worth of segments."""
     K, D = 5, sum(sizes)
     print(f"[case] odd segments K={K} sizes={sizes}", flush=True)
     sw = wl.small_swarm(K, D, seed=21, steps=3)
