@@ -30,7 +30,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 # with: a changed kernel reports null until the counters are taken again.
 MEASURED_TRAFFIC = {
     # profiles/update_kernel_resnet50x32_hbm_traffic.md: mean of three timed launches
-    ("resnet50x32", "8e14e7c189ba7b32"): 16464141000.0,
+    ("resnet50x32", "b787c87e71734db0"): 16460200000.0,
 }
 
 
@@ -78,8 +78,8 @@ def cpu_baseline(cfg, seconds_target: float = 15.0):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="resnet50x32")
     ap.add_argument("--block", type=int, default=0, help="threads per workgroup (0 = default)")
     ap.add_argument("--super-tiles", type=int, default=0)
