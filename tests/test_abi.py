@@ -39,5 +39,8 @@ def test_status_texts_and_argument_checks_without_a_gpu():
     sizes = (ctypes.c_int64 * 2)(4, 5)
     assert lib.pso_ps_create(ctypes.byref(h), 4, 10, 10, 2, sizes, 0) == pso.PSO_PS_EINVAL
     assert lib.pso_ps_sync(None, 0, 0, 0, 0, 0, 0, 0.5, 1.0, 1.0, 0, 0, None) == pso.PSO_PS_EINVAL
+    # a flat index must fit the generator's 32-bit pair counter: D <= 2^33
+    assert lib.pso_ps_create(ctypes.byref(h), 4, (1 << 33) + 1, (1 << 33) + 1, 0, None, 0) \
+        == pso.PSO_PS_EINVAL
     assert lib.pso_ps_destroy(None) == pso.PSO_PS_OK
     assert h.value is None

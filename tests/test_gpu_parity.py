@@ -154,6 +154,62 @@ def test_ties_nan_and_inf_losses(oracle):
         pair.close()
 
 
+def test_subnormal_values_are_kept(oracle):
+    """Positions and velocities in the subnormal range: both sides keep
+    gradual underflow, so the bits still agree."""
+    print("[case] subnormal inputs", flush=True)
+    sw = wl.small_swarm(4, 6000, seed=8, steps=3, x_sigma=3e-39, v_sigma=1e-39)
+    assert np.any((np.abs(sw.x) < 1.1754944e-38) & (sw.x != 0))
+    run_trajectory(oracle, sw, steps=3)
+
+
+def test_non_finite_positions_propagate(oracle):
+    """inf and NaN in x, v: the same elements become NaN/inf on both sides
+    (the bit pattern of a NaN is not part of the contract), the rest agrees in bits."""
+    print("[case] non-finite positions", flush=True)
+    K, D = 4, 5000
+    sw = wl.small_swarm(K, D, seed=9, steps=2)
+    sw.x[1, 7] = np.inf; sw.x[2, 100] = -np.inf; sw.v[3, 4000] = np.nan; sw.x[0, 4999] = np.nan
+    sw.pbest[:] = sw.x
+    pair = gh.Pair(sw)
+    try:
+        for s in range(2):
+            pair.step(oracle, s)
+            for dev_t, host in ((pair.dx, pair.hx), (pair.dv, pair.hv), (pair.dp, pair.hp),
+                                (pair.dg, pair.hg)):
+                got = dev_t.cpu().numpy()
+                assert np.array_equal(np.isnan(got), np.isnan(host))
+                ok = ~np.isnan(host)
+                assert np.array_equal(gh.bits(got)[ok], gh.bits(host)[ok])
+            assert np.isnan(pair.hx).sum() >= 2
+    finally:
+        pair.close()
+
+
+def test_two_handles_on_two_streams(oracle):
+    """Independent swarms on their own handles and streams do not disturb each other."""
+    print("[case] two handles, two streams", flush=True)
+    a, b = wl.small_swarm(5, 30_000, seed=13, steps=4), wl.small_swarm(7, 20_002, seed=14, steps=4)
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(sa):
+        pa = gh.Pair(a)
+    with torch.cuda.stream(sb):
+        pb = gh.Pair(b)
+    try:
+        res = []
+        for s in range(4):
+            with torch.cuda.stream(sa):
+                ra = pa.step(oracle, s)
+            with torch.cuda.stream(sb):
+                rb = pb.step(oracle, s)
+            res.append((ra, rb))
+        torch.cuda.synchronize()
+        pa.check(*res[-1][0], "handle A"); pb.check(*res[-1][1], "handle B")
+    finally:
+        pa.close(); pb.close()
+
+
 def test_deterministic_and_resumable(oracle):
     """Same (seed, step) gives the same bits; five stages, a new handle and
     five more equal ten stages in one go."""

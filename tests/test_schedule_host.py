@@ -8,6 +8,38 @@ import paper_2009_03816_amd as pso
 F32 = np.float32
 
 
+def paper_settings():
+    """tests/golden/paper_settings.txt: the constants of Table II and Section IV."""
+    import os
+    out = {}
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "paper_settings.txt")
+    for line in open(path):
+        if line.strip() and not line.startswith("#"):
+            key, *vals = line.split()
+            out[key] = [float(v) for v in vals] if len(vals) > 1 else float(vals[0])
+    return out
+
+
+def test_paper_settings_give_the_papers_run_lengths(oracle):
+    """With the printed settings: 234 iterations per MNIST epoch (60000/256), Max_t = 5850, a stage
+    every 10th iteration -> 584 stages; inertia runs from just under 0.9 to 0.3 at Max_t; the
+    damping takes c1 = 0.2 down to 0.2/25 in the last epoch."""
+    ps = paper_settings()
+    it = int(ps["mnist_training_size"] // ps["mnist_batch"])
+    ep, step = int(ps["mnist_epochs"]), int(ps["mnist_step"])
+    consts = tuple(F32(ps[k]) for k in ("m_max", "m_min", "c1", "c2"))
+    assert (it, it * ep) == (234, 5850)
+    flags = [pso.pso_ps_schedule(t, it, ep, step, *consts) for t in range(1, it * ep + 1)]
+    assert sum(f[0] for f in flags) == 584
+    assert F32(flags[-1][1]) == F32(0.3) and F32(0.8998) < F32(flags[0][1]) < F32(0.9)
+    assert F32(flags[0][2]) == F32(0.2) and F32(flags[-1][2]) == F32(0.2) / F32(25)
+    assert F32(flags[-1][3]) == F32(0.9) / F32(25)
+    for t in (1, 234, 235, 5850):
+        assert flags[t - 1][0] == oracle.schedule(t, it, ep, step, *consts)[0]
+    it_c = int(ps["cifar_training_size"] // ps["cifar_batch"])
+    assert it_c == 195 and pso.pso_ps_schedule(195 * 30, it_c, 30, 10, *consts)[0] is False
+
+
 def test_inertia_matches_oracle(oracle):
     rng = np.random.default_rng(0)
     for _ in range(3000):
