@@ -177,6 +177,22 @@ def main() -> int:
     achieved = algo_bytes / (avg_ms * 1e-3) / 1e9
     assert bool(torch.isfinite(dx).all()), "state went non-finite"
 
+    # context for the roofline fraction: what a plain device copy of one [K, D]
+    # array reaches on this machine, measured the same way (read + write bytes)
+    if args.variant == "rows":
+        copy_src, copy_dst = torch.stack(xr), torch.empty(K, D, dtype=torch.float32, device=dev)
+    else:
+        copy_src, copy_dst = dx, torch.empty_like(dx)
+    copy_dst.copy_(copy_src)
+    ce = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    ce[0].record(stream)
+    for _ in range(5):
+        copy_dst.copy_(copy_src)
+    ce[1].record(stream)
+    torch.cuda.synchronize()
+    copy_gbs = 5 * 2 * 4.0 * K * D / (ce[0].elapsed_time(ce[1]) * 1e-3) / 1e9
+    del copy_src, copy_dst
+
     if args.copy_probe:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
@@ -197,7 +213,8 @@ def main() -> int:
         "roofline": {"bound": "hbm", "kernel": kernel, "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic, "algorithmic_bytes_per_launch": algo_bytes,
-                     "kernel_ms_avg": avg_ms, "kernel_ms_min": min(kernel_ms)},
+                     "kernel_ms_avg": avg_ms, "kernel_ms_min": min(kernel_ms),
+                     "device_copy_GBps_same_box": copy_gbs},
     }
     torch.cuda.synchronize()
     pso.pso_ps_destroy(h)
