@@ -210,6 +210,48 @@ def test_two_handles_on_two_streams(oracle):
         pa.close(); pb.close()
 
 
+def test_stage_can_be_captured_in_a_hip_graph(oracle):
+    """A stage allocates nothing, copies nothing to the host and clears no
+    memory, so it can be recorded into a HIP graph; every replay (with eager
+    work and synchronisation in between) gives the bits of the eager call."""
+    print("[case] HIP graph capture and replay", flush=True)
+    K, D = 6, 50_002
+    sw = wl.small_swarm(K, D, seed=17, steps=1)
+    loss = gh.to_dev(sw.losses[0])
+
+    def fresh():
+        return [gh.to_dev(a) for a in (sw.x, sw.v, sw.pbest, sw.pbest_loss, np.zeros(D, F32))]
+
+    def stage(h, st):
+        pso.pso_ps_sync(h, st[0], st[1], st[2], st[3], loss, st[4], 0.7, 1.5, 1.5, 17, 3)
+
+    eager, graphed = fresh(), fresh()
+    he, hg = pso.pso_ps_create(K, D), pso.pso_ps_create(K, D)
+    try:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            stage(hg, graphed)                        # warm-up outside the capture
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        for t, src in zip(graphed, fresh()):
+            t.copy_(src)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            stage(hg, graphed)                        # recorded, not run
+        for replay in range(3):
+            stage(he, eager)
+            graph.replay()
+            torch.cuda.synchronize()
+            scratch = torch.randn(1000, device=gh.dev()).sum().item()   # eager work in between
+            assert scratch == scratch
+            for te, tg in zip(eager, graphed):
+                assert torch.equal(te.view(torch.int32), tg.view(torch.int32)), f"replay {replay}"
+    finally:
+        torch.cuda.synchronize()
+        pso.pso_ps_destroy(he); pso.pso_ps_destroy(hg)
+
+
 def test_deterministic_and_resumable(oracle):
     """Same (seed, step) gives the same bits; five stages, a new handle and
     five more equal ten stages in one go."""
