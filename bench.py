@@ -92,7 +92,7 @@ def main() -> int:
                     help="also launch one plain device copy of 1 GiB (counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); "
+        print("bench.py: this library runs on ONE GPU (no collectives, no sharding); "
               "--gpus must be 1", file=sys.stderr)
         return 2
 

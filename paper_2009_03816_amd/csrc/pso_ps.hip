@@ -45,6 +45,7 @@
 #include <vector>
 
 #include "pso_ps.h"
+#include "tile_order.h"
 
 namespace {
 
@@ -94,21 +95,6 @@ struct MoveParams {
     float w, c1, c2;            // inertia (paper's m), effective accelerations
     uint32_t key0, key1;        // seed halves  -> Philox key
     uint32_t step_lo, step_hi;  // step halves  -> Philox counter words 2, 3
-};
-
-// Workgroup order of the update pass.  Workgroup b belongs to XCD b & 7 and is
-// the (b >> 3)-th of that XCD.  An XCD owns the tile chunks m with m % 8 == xcd
-// (a chunk is 2^chunk_log2 consecutive tiles), listed as u = 0 .. per_xcd-1.  The
-// list is cut into super-chunks of 2^super_log2 entries (the last one may be
-// shorter); within a super-chunk the order is row-major: all its tiles for row
-// 0, then for row 1, ...
-struct TileOrder {
-    unsigned tiles;       // tiles per row (address-aligned tiles, first/last partial)
-    unsigned per_xcd;     // list length per XCD (multiple of the chunk size)
-    unsigned super_log2;
-    unsigned chunk_log2;
-    unsigned full;        // number of full super-chunks
-    unsigned last;        // entries in the last, shorter super-chunk (0 if none)
 };
 
 // Ragged mode: up to kTableSegs dense [K, n] segments share one launch.  Each
@@ -241,32 +227,6 @@ __device__ __forceinline__ void move_quad(const RowPtrs& r, const float* __restr
     if (improved) __builtin_nontemporal_store(x_old, reinterpret_cast<f32x4*>(pp));
 }
 
-// Which (row, tile) does workgroup `wg` of a launch (or of a segment's share of
-// a launch, which starts at a multiple of 8) handle?  `rows` rows share the
-// order.  Returns false for the padding workgroups at the end of an XCD's list.
-__device__ __forceinline__ bool decode_workgroup(const TileOrder& ord, unsigned rows, unsigned wg,
-                                                 unsigned* row, unsigned* tile) {
-    const unsigned xcd = wg & 7u;
-    const unsigned j = wg >> 3;
-    const unsigned super = 1u << ord.super_log2;
-    const unsigned full_span = (ord.full << ord.super_log2) * rows;
-    unsigned i, u;
-    if (j < full_span) {
-        const unsigned q = j >> ord.super_log2;  // (super-chunk, row) pair
-        const unsigned sc = q / rows;
-        i = q - sc * rows;
-        u = (sc << ord.super_log2) + (j & (super - 1u));
-    } else {
-        const unsigned r = j - full_span;
-        i = r / ord.last;
-        u = (ord.full << ord.super_log2) + (r - i * ord.last);
-    }
-    const unsigned chunk_mask = (1u << ord.chunk_log2) - 1u;
-    *tile = ((((u >> ord.chunk_log2) << 3) + xcd) << ord.chunk_log2) + (u & chunk_mask);
-    *row = i;
-    return *tile < ord.tiles && i < rows;
-}
-
 // One row x one tile.  VEC: x, v, pbest of the row are congruent modulo 16
 // bytes and (d0 + element address of x) is even, so that an address-aligned
 // group of four floats is two whole Philox pairs; tiles are then aligned to the
@@ -302,7 +262,7 @@ __global__ __launch_bounds__(BLOCK) void update_kernel(ColumnBlock b, int K,
                                                        float* gbest_loss) {
     if (gbest_loss && blockIdx.x == 0 && threadIdx.x == 0) *gbest_loss = sel->gbest_loss;
     unsigned i, tile;
-    if (!decode_workgroup(ord, (unsigned)K, blockIdx.x, &i, &tile)) return;
+    if (!decode_tile_order(ord, (unsigned)K, blockIdx.x, &i, &tile)) return;
     const long long row = (long long)i * b.ld;
     const RowPtrs r{b.x + row, b.v + row, b.pbest + row};
     update_tile<BLOCK, VEC>(r, b.gbest, b.n, b.d0, i, tile, is_improved(sel, (int)i), m);
@@ -315,7 +275,7 @@ __global__ __launch_bounds__(BLOCK) void update_rows_kernel(RowTable tab, const 
                                                             const Selection* __restrict__ sel,
                                                             MoveParams m, TileOrder ord) {
     unsigned i, tile;
-    if (!decode_workgroup(ord, (unsigned)rows, blockIdx.x, &i, &tile)) return;
+    if (!decode_tile_order(ord, (unsigned)rows, blockIdx.x, &i, &tile)) return;
     const RowPtrs r{tab.x[i], tab.v[i], tab.pbest[i]};
     const unsigned particle = (unsigned)row0 + i;
     update_tile<BLOCK, VEC>(r, gbest, n, 0ull, particle, tile, is_improved(sel, (int)particle), m);
@@ -342,7 +302,7 @@ __global__ __launch_bounds__(BLOCK) void update_segments_kernel(SegTable tab, in
                                                                 MoveParams m) {
     const SegEntry e = segment_of<false>(tab, blockIdx.x);
     unsigned i, tile;
-    if (!decode_workgroup(e.ord, (unsigned)K, blockIdx.x - e.first_update_wg, &i, &tile)) return;
+    if (!decode_tile_order(e.ord, (unsigned)K, blockIdx.x - e.first_update_wg, &i, &tile)) return;
     const long long row = (long long)i * e.n;  // segments are dense: row stride = n
     const RowPtrs r{e.x + row, e.v + row, e.pbest + row};
     const bool improved = is_improved(sel, (int)i);
@@ -516,7 +476,7 @@ __global__ __launch_bounds__(BLOCK) void broadcast_kernel(float* x, const float*
                                                           TileOrder ord) {
     constexpr unsigned TILE = BLOCK * 4;
     unsigned i, tile;
-    if (!decode_workgroup(ord, (unsigned)K, blockIdx.x, &i, &tile)) return;
+    if (!decode_tile_order(ord, (unsigned)K, blockIdx.x, &i, &tile)) return;
     float* row = x + (long long)i * ld;
     long long phase = 0;
     if (VEC) phase = (long long)((reinterpret_cast<uintptr_t>(row) >> 2) & (TILE - 1u));
@@ -536,12 +496,6 @@ __global__ __launch_bounds__(BLOCK) void broadcast_kernel(float* x, const float*
 // ---------------------------------------------------------------------------
 bool aligned_to(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
-unsigned ceil_log2(unsigned long long t) {
-    unsigned l = 0;
-    while ((1ull << l) < t) ++l;
-    return l;
-}
-
 }  // namespace
 
 struct pso_ps_ctx {
@@ -549,6 +503,11 @@ struct pso_ps_ctx {
     int64_t D;
     int64_t ld;
     std::vector<int64_t> seg_sizes;  // empty: one flat block
+    // Work lists of pso_ps_sync_segments, sized at create so that a stage does
+    // not touch the host heap.
+    std::vector<ColumnBlock> seg_blocks;
+    std::vector<SegTable> seg_tables;
+    std::vector<unsigned> seg_update_wgs, seg_copy_wgs;
     int device;
     Selection* sel;        // device
     size_t sel_bytes;
@@ -624,30 +583,15 @@ bool block_vector_ok(const pso_ps_ctx* h, const ColumnBlock& b) {
     return row_vector_ok(b.x, b.v, b.pbest, b.d0);
 }
 
-// Workgroup order for `rows` rows of n columns whose address-aligned tiling
-// needs `tiles` tiles per row.  Returns false if the grid would be too large.
+// Workgroup order for `rows` rows of `tiles` tiles of `tile` floats, with the
+// handle's launch settings.  Returns false if the grid would be too large.
 bool plan_order(const pso_ps_ctx* h, int rows, unsigned long long tiles, unsigned tile,
                 TileOrder* ord, unsigned long long* grid) {
-    // Large blocks: XCD-aware super-chunks.  Small ones: plain row-major order,
-    // which is the special case "one super-chunk, chunks of one tile".
-    unsigned long long super = h->super_tiles ? (unsigned long long)h->super_tiles
-                                              : kDefaultSuperBytes / (tile * 4u);
-    unsigned long long chunk = h->chunk_tiles ? (unsigned long long)h->chunk_tiles
-                                              : kDefaultChunkBytes / (tile * 4u);
-    if (chunk > super) chunk = super;
-    if (tiles < 16ull * super) chunk = 1;  // keep all eight XCDs evenly loaded
-    const unsigned long long per_xcd = (tiles + 8 * chunk - 1) / (8 * chunk) * chunk;
-    if (!h->super_tiles && tiles < 16ull * super) super = 1ull << ceil_log2(per_xcd);
-    if (tiles >= (1ull << 31) || per_xcd * 8ull * (unsigned long long)rows >= (1ull << 31))
-        return false;
-    ord->tiles = (unsigned)tiles;
-    ord->per_xcd = (unsigned)per_xcd;
-    ord->super_log2 = ceil_log2(super);
-    ord->chunk_log2 = ceil_log2(chunk);
-    ord->full = (unsigned)(per_xcd >> ord->super_log2);
-    ord->last = (unsigned)(per_xcd - ((unsigned long long)ord->full << ord->super_log2));
-    *grid = per_xcd * 8ull * (unsigned long long)rows;
-    return true;
+    const unsigned long long super = h->super_tiles ? (unsigned long long)h->super_tiles
+                                                    : kDefaultSuperBytes / (tile * 4u);
+    const unsigned long long chunk = h->chunk_tiles ? (unsigned long long)h->chunk_tiles
+                                                    : kDefaultChunkBytes / (tile * 4u);
+    return plan_tile_order(rows, tiles, super, chunk, h->super_tiles != 0, ord, grid);
 }
 
 // Tiles per row: with the vector path tiles are aligned to each row's address.
@@ -801,7 +745,14 @@ int pso_ps_create(pso_ps_ctx** out, int K, int64_t D, int64_t ld, int n_seg,
     if (!h) return PSO_PS_ENOMEM;
     h->K = K; h->D = D; h->ld = ld; h->device = device;
     try {
-        if (n_seg > 0) h->seg_sizes.assign(seg_sizes, seg_sizes + n_seg);
+        if (n_seg > 0) {
+            h->seg_sizes.assign(seg_sizes, seg_sizes + n_seg);
+            const size_t launches = ((size_t)n_seg + kTableSegs - 1) / kTableSegs;
+            h->seg_blocks.reserve((size_t)n_seg);
+            h->seg_tables.reserve(launches);
+            h->seg_update_wgs.reserve(launches);
+            h->seg_copy_wgs.reserve(launches);
+        }
     } catch (...) {
         delete h;
         return PSO_PS_ENOMEM;
@@ -876,14 +827,13 @@ int pso_ps_sync_segments(pso_ps_ctx* h, float* const* x_seg, float* const* v_seg
     if (h->seg_sizes.empty()) return PSO_PS_EINVAL;
     if (!aligned_to(pbest_loss, 4) || !aligned_to(loss, 4)) return PSO_PS_EALIGN;
     const int n_seg = (int)h->seg_sizes.size();
-    // Validate every segment before anything is enqueued.
-    std::vector<ColumnBlock> blocks;
-    std::vector<unsigned> update_totals, copy_totals;
-    try {
-        blocks.reserve((size_t)n_seg);
-    } catch (...) {
-        return PSO_PS_ENOMEM;
-    }
+    // Validate every segment before anything is enqueued.  The work lists were
+    // reserved at create: no allocation happens here.
+    std::vector<ColumnBlock>& blocks = h->seg_blocks;
+    std::vector<SegTable>& tables = h->seg_tables;
+    std::vector<unsigned>& update_totals = h->seg_update_wgs;
+    std::vector<unsigned>& copy_totals = h->seg_copy_wgs;
+    blocks.clear(); tables.clear(); update_totals.clear(); copy_totals.clear();
     unsigned long long start = 0;
     for (int s = 0; s < n_seg; ++s) {
         const long long n = (long long)h->seg_sizes[s];
@@ -902,43 +852,37 @@ int pso_ps_sync_segments(pso_ps_ctx* h, float* const* x_seg, float* const* v_seg
     const int block = h->block_threads ? h->block_threads : kDefaultBlock;
     // Up to kTableSegs segments per launch; the selection rides on the first
     // gbest-copy launch.  All copies are enqueued before the first update.
-    std::vector<SegTable> tables;
-    try {
-        tables.reserve((blocks.size() + kTableSegs - 1) / kTableSegs);
-        for (size_t first = 0; first < blocks.size(); first += kTableSegs) {
-            SegTable tab;
-            tab.count = (int)((blocks.size() - first < (size_t)kTableSegs) ? blocks.size() - first
-                                                                          : (size_t)kTableSegs);
-            unsigned long long update_wg = 0, copy_wg = 0;
-            for (int s = 0; s < kTableSegs; ++s) {
-                SegEntry& e = tab.seg[s];
-                if (s >= tab.count) {
-                    e = tab.seg[tab.count - 1];
-                    continue;
-                }
-                const ColumnBlock& b = blocks[first + s];
-                e.x = b.x; e.v = b.v; e.pbest = b.pbest; e.gbest = b.gbest;
-                e.n = b.n; e.d0 = b.d0; e.reserved = 0;
-                e.vec = block_vector_ok(h, b) ? 1 : 0;
-                const unsigned tile = (unsigned)block * 4u;
-                const unsigned long long tiles = tiles_per_row(
-                    h->K, b.n, e.vec != 0, tile, [&](int i) { return b.x + (long long)i * b.ld; });
-                unsigned long long grid = 0;
-                if (!plan_order(h, h->K, tiles, tile, &e.ord, &grid))
-                    return hip_fail(h, hipErrorInvalidConfiguration);
-                e.first_update_wg = (unsigned)update_wg;
-                e.first_copy_wg = (unsigned)copy_wg;
-                update_wg += grid;
-                copy_wg += (unsigned long long)((b.n + 4LL * kCopyBlock - 1) / (4LL * kCopyBlock));
-                if (update_wg >= (1ull << 31) || copy_wg >= (1ull << 31))
-                    return hip_fail(h, hipErrorInvalidConfiguration);
+    for (size_t first = 0; first < blocks.size(); first += kTableSegs) {
+        SegTable tab;
+        tab.count = (int)((blocks.size() - first < (size_t)kTableSegs) ? blocks.size() - first
+                                                                      : (size_t)kTableSegs);
+        unsigned long long update_wg = 0, copy_wg = 0;
+        for (int s = 0; s < kTableSegs; ++s) {
+            SegEntry& e = tab.seg[s];
+            if (s >= tab.count) {
+                e = tab.seg[tab.count - 1];  // never selected: segment_of stops at count
+                continue;
             }
-            tables.push_back(tab);
-            update_totals.push_back((unsigned)update_wg);
-            copy_totals.push_back((unsigned)copy_wg);
+            const ColumnBlock& b = blocks[first + s];
+            e.x = b.x; e.v = b.v; e.pbest = b.pbest; e.gbest = b.gbest;
+            e.n = b.n; e.d0 = b.d0; e.reserved = 0;
+            e.vec = block_vector_ok(h, b) ? 1 : 0;
+            const unsigned tile = (unsigned)block * 4u;
+            const unsigned long long tiles = tiles_per_row(
+                h->K, b.n, e.vec != 0, tile, [&](int i) { return b.x + (long long)i * b.ld; });
+            unsigned long long grid = 0;
+            if (!plan_order(h, h->K, tiles, tile, &e.ord, &grid))
+                return hip_fail(h, hipErrorInvalidConfiguration);
+            e.first_update_wg = (unsigned)update_wg;
+            e.first_copy_wg = (unsigned)copy_wg;
+            update_wg += grid;
+            copy_wg += (unsigned long long)((b.n + 4LL * kCopyBlock - 1) / (4LL * kCopyBlock));
+            if (update_wg >= (1ull << 31) || copy_wg >= (1ull << 31))
+                return hip_fail(h, hipErrorInvalidConfiguration);
         }
-    } catch (...) {
-        return PSO_PS_ENOMEM;
+        tables.push_back(tab);
+        update_totals.push_back((unsigned)update_wg);
+        copy_totals.push_back((unsigned)copy_wg);
     }
     for (size_t t = 0; t < tables.size(); ++t) {
         hipLaunchKernelGGL(select_gbest_segments_kernel<kCopyBlock>, dim3(copy_totals[t]),
