@@ -35,9 +35,14 @@ MEASURED_TRAFFIC = {
 
 
 def kernel_source_hash() -> str:
+    """Hash of every file under csrc/ (kernels, their headers, the host launch code)."""
     from paper_2009_03816_amd import build
-    with open(build.SOURCE, "rb") as f:
-        return hashlib.sha256(f.read()).hexdigest()[:16]
+    csrc = os.path.dirname(build.SOURCE)
+    digest = hashlib.sha256()
+    for name in sorted(os.listdir(csrc)):
+        with open(os.path.join(csrc, name), "rb") as f:
+            digest.update(name.encode() + b"\0" + f.read())
+    return digest.hexdigest()[:16]
 
 
 def cpu_baseline(cfg, seconds_target: float = 15.0):
