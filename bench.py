@@ -89,9 +89,11 @@ def main() -> int:
     ap.add_argument("--block", type=int, default=0, help="threads per workgroup (0 = default)")
     ap.add_argument("--super-tiles", type=int, default=0)
     ap.add_argument("--chunk-tiles", type=int, default=0)
-    ap.add_argument("--variant", default="sync", choices=["sync", "history", "rows", "average"],
+    ap.add_argument("--variant", default="sync", choices=["sync", "history", "rows", "segments", "average"],
                     help="sync: the stage (default, the headline); history: historical gBest; "
-                         "rows: K separate per-worker arrays; average: parameter averaging")
+                         "rows: K separate per-worker arrays; segments: one [K, n] array per "
+                         "parameter tensor (needs a workload with a segment list); "
+                         "average: parameter averaging")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch one plain device copy of 1 GiB (counter calibration)")
@@ -120,6 +122,15 @@ def main() -> int:
         vr = [torch.from_numpy(sw.v[i]).to(dev) for i in range(K)]
         pr = [t.clone() for t in xr]
         dx = xr[0]
+    elif args.variant == "segments":                     # one dense [K, n] array per tensor
+        if not cfg.segments:
+            print(f"bench.py: workload {cfg.name} has no segment list", file=sys.stderr)
+            return 2
+        xs = [torch.from_numpy(a).to(dev) for a in wl.segment_views(sw.x, cfg.segments)]
+        vs = [torch.from_numpy(a).to(dev) for a in wl.segment_views(sw.v, cfg.segments)]
+        ps = [t.clone() for t in xs]
+        gs = [torch.zeros(n, dtype=torch.float32, device=dev) for n in cfg.segments]
+        dx = max(xs, key=lambda t: t.numel())
     else:
         dx = torch.from_numpy(sw.x).to(dev)
         dv = torch.from_numpy(sw.v).to(dev)
@@ -131,7 +142,8 @@ def main() -> int:
     w_tab, c1, c2 = [float(t) for t in sw.w], float(sw.c1), float(sw.c2)
     del sw
 
-    h = pso.pso_ps_create(K, D)
+    h = pso.pso_ps_create(K, D, D, seg_sizes=list(cfg.segments)) if args.variant == "segments" \
+        else pso.pso_ps_create(K, D)
     if args.block or args.super_tiles or args.chunk_tiles:
         pso.pso_ps_set_launch(h, args.block, args.super_tiles, args.chunk_tiles, False)
     stream = torch.cuda.current_stream()
@@ -151,6 +163,9 @@ def main() -> int:
         elif args.variant == "rows":
             pso.pso_ps_sync_rows(h, xr, vr, pr, dpl, dloss[s], dg, w_tab[s], c1, c2, cfg.seed, s,
                                  stream)
+        elif args.variant == "segments":
+            pso.pso_ps_sync_segments(h, xs, vs, ps, dpl, dloss[s], gs, w_tab[s], c1, c2,
+                                     cfg.seed, s, stream)
         else:
             pso.pso_ps_average(h, dx, dg, stream)
         if ev:
@@ -177,8 +192,9 @@ def main() -> int:
         kernel = "update_kernel"
     else:
         algo_bytes = 4.0 * D * (5 * K + 3)               # whole call: + read x_g, write gbest
-        kernel = "select_gbest_kernel + " + ("update_rows_kernel" if args.variant == "rows"
-                                             else "update_kernel")
+        kernel = {"rows": "select_gbest_kernel + update_rows_kernel",
+                  "segments": "select_gbest_segments_kernel + update_segments_kernel",
+                  "history": "select_gbest_kernel + update_kernel"}[args.variant]
     achieved = algo_bytes / (avg_ms * 1e-3) / 1e9
     assert bool(torch.isfinite(dx).all()), "state went non-finite"
 
@@ -186,6 +202,9 @@ def main() -> int:
     # array reaches on this machine, measured the same way (read + write bytes)
     if args.variant == "rows":
         copy_src, copy_dst = torch.stack(xr), torch.empty(K, D, dtype=torch.float32, device=dev)
+    elif args.variant == "segments":
+        copy_src = torch.cat([t.reshape(-1) for t in xs])
+        copy_dst = torch.empty_like(copy_src)
     else:
         copy_src, copy_dst = dx, torch.empty_like(dx)
     copy_dst.copy_(copy_src)

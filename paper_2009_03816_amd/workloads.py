@@ -24,6 +24,34 @@ import numpy as np
 LENET5_SEGMENTS = (6 * 1 * 5 * 5, 6, 16 * 6 * 5 * 5, 16, 400 * 120, 120, 120 * 84, 84, 84 * 10, 10)
 
 
+def resnet50_segments() -> Tuple[int, ...]:
+    """Sizes of the 161 parameter tensors of a ResNet-50 classifier (1000
+    classes) in registration order: 7x7 stem, four stages of 3/4/6/3 bottleneck
+    blocks (1x1, 3x3, 1x1 convolutions, each followed by a batch-norm weight and
+    bias; a 1x1 projection in the first block of a stage), and the final linear
+    layer.  They sum to 25,557,032."""
+    sizes = []
+
+    def conv(cout, cin, k):
+        sizes.append(cout * cin * k * k)
+
+    def bn(c):
+        sizes.extend([c, c])
+
+    conv(64, 3, 7); bn(64)
+    inplanes = 64
+    for planes, blocks in ((64, 3), (128, 4), (256, 6), (512, 3)):
+        for b in range(blocks):
+            conv(planes, inplanes, 1); bn(planes)
+            conv(planes, planes, 3); bn(planes)
+            conv(planes * 4, planes, 1); bn(planes * 4)
+            if b == 0:
+                conv(planes * 4, inplanes, 1); bn(planes * 4)
+            inplanes = planes * 4
+    sizes.extend([1000 * 2048, 1000])
+    return tuple(sizes)
+
+
 @dataclass(frozen=True)
 class SwarmConfig:
     name: str
@@ -57,6 +85,10 @@ CONFIGS = {
                                loss=("uniform", 0.5, 7.0), w=(0.72, 0.72), c1=1.49, c2=1.49,
                                steps=10, seed=4),
 }
+# The same swarm held as one dense [K, n] array per parameter tensor (161 of them).
+CONFIGS["resnet50x32_layers"] = SwarmConfig(
+    **{**CONFIGS["resnet50x32"].__dict__, "name": "resnet50x32_layers",
+       "segments": resnet50_segments()})
 
 
 @dataclass

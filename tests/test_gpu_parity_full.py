@@ -71,3 +71,57 @@ def test_full_size_config(oracle, name):
     finally:
         torch.cuda.synchronize()
         pso.pso_ps_destroy(h)
+
+
+def test_full_size_per_layer_layout(oracle):
+    """The large swarm held as 161 per-tensor [K, n] arrays (11 launches' worth
+    of segments): windows of a small, a mid-sized, the largest and the last
+    tensors against the oracle, every array against the flat call's properties."""
+    cfg = wl.CONFIGS["resnet50x32_layers"]
+    K, D, sizes = cfg.K, cfg.D, list(cfg.segments)
+    print(f"[case] full-size per-layer layout: K={K} D={D} in {len(sizes)} tensors", flush=True)
+    sw = wl.make_swarm(cfg, steps=3)
+    starts = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    big = int(np.argmax(sizes))
+    picks = [(0, 0, sizes[0]), (1, 0, sizes[1]), (3, 0, 3000), (big, 0, 2500),
+             (big, sizes[big] // 2 - 999, sizes[big] // 2 + 1200), (big, sizes[big] - 2048, sizes[big]),
+             (len(sizes) - 2, 1_000_001, 1_003_000), (len(sizes) - 1, 0, sizes[-1])]
+    host = []
+    for s, lo, hi in picks:
+        a, b = starts[s] + lo, starts[s] + hi
+        host.append([np.ascontiguousarray(t[:, a:b]) for t in (sw.x, sw.v, sw.pbest)])
+    hpl = [sw.pbest_loss.copy() for _ in picks]
+    xs = [torch.from_numpy(a).to(gh.dev()) for a in wl.segment_views(sw.x, sizes)]
+    vs = [torch.from_numpy(a).to(gh.dev()) for a in wl.segment_views(sw.v, sizes)]
+    ps = [t.clone() for t in xs]
+    gs = [torch.zeros(n, dtype=torch.float32, device=gh.dev()) for n in sizes]
+    dpl = gh.to_dev(sw.pbest_loss)
+    losses, c1, c2 = sw.losses, float(sw.c1), float(sw.c2)
+    w_tab = sw.w
+    del sw
+    gc.collect()
+    h = pso.pso_ps_create(K, D, D, seg_sizes=sizes)
+    try:
+        for step in range(3):
+            x_old = [t.clone() for t in xs]
+            w = float(w_tab[step])
+            pso.pso_ps_sync_segments(h, xs, vs, ps, dpl, gh.to_dev(losses[step]), gs, w, c1, c2,
+                                     cfg.seed, step)
+            g_dev, imp_dev = pso.pso_ps_last_selection(h, K)
+            for (s, lo, hi), (hx, hv, hp), pl in zip(picks, host, hpl):
+                hg = np.empty(hi - lo, F32)
+                g, improved = oracle.sync(hx, hv, hp, pl, losses[step], hg, F32(w), F32(c1), F32(c2),
+                                          cfg.seed, step, d0=int(starts[s]) + lo)
+                what = f"per-layer step {step} tensor {s} columns [{lo},{hi})"
+                assert g_dev == g and imp_dev == [bool(t) for t in improved], what
+                gh.assert_bits_equal(gs[s][lo:hi].cpu().numpy(), hg, what + ": gbest")
+                gh.assert_bits_equal(ps[s][:, lo:hi].cpu().numpy(), hp, what + ": pbest")
+                gh.assert_close(xs[s][:, lo:hi].cpu().numpy(), hx, what + ": x")
+                gh.assert_close(vs[s][:, lo:hi].cpu().numpy(), hv, what + ": v")
+            for s in range(len(sizes)):
+                assert torch.equal(gs[s].view(torch.int32), x_old[s][g_dev].view(torch.int32))
+                assert torch.equal(xs[s], x_old[s] + vs[s]), f"tensor {s}: x' != x + v'"
+            print(f"[case] per-layer step {step} ok (g={g_dev}, improved={sum(imp_dev)})", flush=True)
+    finally:
+        torch.cuda.synchronize()
+        pso.pso_ps_destroy(h)

@@ -13,6 +13,9 @@ def test_config_shapes():
     assert (c["resnet20"].K, c["resnet20"].D) == (16, 272_474)
     assert (c["vgg16"].K, c["vgg16"].D) == (8, 14_728_266)
     assert (c["resnet50x32"].K, c["resnet50x32"].D) == (32, 25_557_032)
+    layers = c["resnet50x32_layers"]
+    assert len(layers.segments) == 161 and sum(layers.segments) == layers.D == 25_557_032
+    assert layers.segments[0] == 64 * 3 * 49 and layers.segments[-2:] == (2_048_000, 1000)
 
 
 def test_seeded_and_initial_state():
