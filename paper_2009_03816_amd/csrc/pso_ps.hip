@@ -518,6 +518,7 @@ struct pso_ps_ctx {
     int super_tiles;       // 0 = default; else a power of two
     int chunk_tiles;       // 0 = default; else a power of two <= super_tiles
     bool force_generic;
+    bool eight_xcds;       // 256 compute units: the chip is driven as one device of 8 XCDs
     int last_hip_error;
 };
 
@@ -591,6 +592,11 @@ bool plan_order(const pso_ps_ctx* h, int rows, unsigned long long tiles, unsigne
                                                     : kDefaultSuperBytes / (tile * 4u);
     const unsigned long long chunk = h->chunk_tiles ? (unsigned long long)h->chunk_tiles
                                                     : kDefaultChunkBytes / (tile * 4u);
+    // The chunked order is tuned for workgroups dealt round-robin to 8 XCDs.  On
+    // a partitioned device (fewer compute units behind one device) fall back to
+    // plain row-major order unless the caller has chosen a shape.
+    if (!h->eight_xcds && !h->super_tiles && !h->chunk_tiles)
+        return plan_tile_order(rows, tiles, 1ull << 30, 1, false, ord, grid);
     return plan_tile_order(rows, tiles, super, chunk, h->super_tiles != 0, ord, grid);
 }
 
@@ -761,10 +767,14 @@ int pso_ps_create(pso_ps_ctx** out, int K, int64_t D, int64_t ld, int n_seg,
     h->sel_bytes = sizeof(Selection) + (size_t)(h->mask_words - 1) * sizeof(uint64_t);
     h->sel = nullptr; h->last_stream = nullptr; h->have_selection = false;
     h->block_threads = 0; h->super_tiles = 0; h->chunk_tiles = 0;
-    h->force_generic = false; h->last_hip_error = 0;
+    h->force_generic = false; h->eight_xcds = true; h->last_hip_error = 0;
 
     DeviceScope scope(device);
     hipError_t e = scope.err;
+    int compute_units = 0;
+    if (e == hipSuccess)
+        e = hipDeviceGetAttribute(&compute_units, hipDeviceAttributeMultiprocessorCount, device);
+    h->eight_xcds = compute_units == 256;
     if (e == hipSuccess) e = hipMalloc((void**)&h->sel, h->sel_bytes);
     if (e == hipSuccess) e = hipMemset(h->sel, 0, h->sel_bytes);
     if (e != hipSuccess) {

@@ -154,6 +154,59 @@ def test_ties_nan_and_inf_losses(oracle):
         pair.close()
 
 
+def test_random_shapes_alignments_and_layouts(oracle):
+    """Sixty seeded random cases: K, D, row stride, buffer offsets (which pick
+    the 128-bit or the element-wise path and shift the tile phase), launch shape,
+    and for every third case a ragged split of the columns."""
+    rng = np.random.default_rng(2009_03816)
+    for case in range(60):
+        K = int(rng.choice([1, 2, 3, 5, 8, 17, 33, 70]))
+        D = int(rng.integers(1, 6000))
+        ld = D + int(rng.choice([0, 0, 1, 2, 3, 4, 30]))
+        offset = int(rng.choice([0, 0, 1, 2, 3, 4, 32, 258]))
+        block = int(rng.choice([0, 64, 128, 256, 1024]))
+        sup = int(rng.choice([0, 0, 1, 2, 8]))
+        chunk = int(rng.choice([0, 1, 2, 4])) if sup else 0
+        seed = int(rng.integers(0, 2 ** 62))
+        print(f"[case] random {case}: K={K} D={D} ld={ld} offset={offset} block={block} "
+              f"super={sup} chunk={chunk}", flush=True)
+        sw = wl.small_swarm(K, D, seed=1000 + case, ld=ld, steps=2)
+        if case % 3 == 2 and D >= 4:
+            cuts = np.sort(rng.choice(np.arange(1, D), size=min(D - 1, int(rng.integers(1, 6))),
+                                      replace=False))
+            sizes = [int(t) for t in np.diff(np.concatenate([[0], cuts, [D]]))]
+            hx, hv, hp = sw.x[:, :D].copy(), sw.v[:, :D].copy(), sw.pbest[:, :D].copy()
+            hpl, hg = sw.pbest_loss.copy(), np.zeros(D, F32)
+            dx, dv, dp = ([gh.to_dev(a, offset) for a in wl.segment_views(t, sizes)]
+                          for t in (hx, hv, hp))
+            dg = [gh.to_dev(np.zeros(n, F32), offset) for n in sizes]
+            dpl = gh.to_dev(hpl)
+            h = pso.pso_ps_create(K, D, D, seg_sizes=sizes)
+            try:
+                pso.pso_ps_set_launch(h, block, sup, chunk, False)
+                for s in range(2):
+                    pso.pso_ps_sync_segments(h, dx, dv, dp, dpl, gh.to_dev(sw.losses[s]), dg,
+                                             0.7, 1.5, 1.5, seed, s)
+                    oracle.sync(hx, hv, hp, hpl, sw.losses[s], hg, F32(0.7), F32(1.5), F32(1.5),
+                                seed, s)
+                cat = lambda parts: np.concatenate([t.cpu().numpy() for t in parts], axis=-1)
+                gh.assert_bits_equal(cat(dp), hp, f"random {case}: pbest")
+                gh.assert_bits_equal(cat(dg), hg, f"random {case}: gbest")
+                gh.assert_close(cat(dx), hx, f"random {case}: x")
+                gh.assert_close(cat(dv), hv, f"random {case}: v")
+            finally:
+                torch.cuda.synchronize()
+                pso.pso_ps_destroy(h)
+        else:
+            pair = gh.Pair(sw, offset=offset, block_threads=block, super_tiles=sup, chunk_tiles=chunk)
+            try:
+                for s in range(2):
+                    g, improved = pair.step(oracle, s, seed=seed)
+                pair.check(g, improved, f"random {case}")
+            finally:
+                pair.close()
+
+
 def test_subnormal_values_are_kept(oracle):
     """Positions and velocities in the subnormal range: both sides keep
     gradual underflow, so the bits still agree."""
