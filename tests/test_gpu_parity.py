@@ -207,6 +207,31 @@ def test_random_shapes_alignments_and_layouts(oracle):
                 pair.close()
 
 
+def test_seed_and_step_use_all_64_bits(oracle):
+    print("[case] 64-bit seed and step", flush=True)
+    K, D = 3, 4100
+    sw = wl.small_swarm(K, D, seed=19, steps=1)
+    results = []
+    for seed, step in [((1 << 63) + 5, (1 << 40) + 3), (5, (1 << 40) + 3), ((1 << 63) + 5, 3), (5, 3)]:
+        host = [sw.x.copy(), sw.v.copy(), sw.pbest.copy(), sw.pbest_loss.copy(), np.zeros(D, F32)]
+        dev = [gh.to_dev(a) for a in host]
+        h = pso.pso_ps_create(K, D)
+        try:
+            pso.pso_ps_sync(h, dev[0], dev[1], dev[2], dev[3], gh.to_dev(sw.losses[0]), dev[4],
+                            0.7, 1.5, 1.5, seed, step)
+            oracle.sync(host[0], host[1], host[2], host[3], sw.losses[0], host[4], F32(0.7), F32(1.5),
+                        F32(1.5), seed, step)
+            gh.assert_close(dev[0].cpu().numpy(), host[0], f"seed {seed} step {step}: x")
+            gh.assert_close(dev[1].cpu().numpy(), host[1], f"seed {seed} step {step}: v")
+            results.append(host[1].copy())
+        finally:
+            torch.cuda.synchronize()
+            pso.pso_ps_destroy(h)
+    for a in range(4):
+        for b in range(a + 1, 4):
+            assert not np.array_equal(results[a], results[b])   # the high halves matter
+
+
 def test_subnormal_values_are_kept(oracle):
     """Positions and velocities in the subnormal range: both sides keep
     gradual underflow, so the bits still agree."""
