@@ -66,19 +66,22 @@ def cpu_baseline(cfg, seconds_target: float = 15.0):
         rate = cfg.K * nc / (time.perf_counter() - t0)
     n = int(min(cfg.D, max(1024, seconds_target * rate / cfg.K)))
     n -= n % 2
+    stages = int(max(1, min(4, round(seconds_target * rate / (cfg.K * n)))))
     rng = np.random.default_rng(cfg.seed)
-    losses = wl.draw_losses(cfg, rng, 2)
+    losses = wl.draw_losses(cfg, rng, stages + 1)
     x = (rng.standard_normal((cfg.K, n), dtype=np.float32) * np.float32(cfg.x_sigma))
     v = (rng.standard_normal((cfg.K, n), dtype=np.float32) * np.float32(cfg.v_sigma))
     pbest = x.copy()
     pbest_loss = np.minimum(losses[0], np.float32(3.0))  # about half of the particles improve
     gbest = np.empty(n, np.float32)
     t0 = time.perf_counter()
-    oracle.sync(x, v, pbest, pbest_loss, losses[1], gbest, np.float32(cfg.w[0]),
-                np.float32(cfg.c1), np.float32(cfg.c2), cfg.seed, 0)
+    for s in range(stages):
+        oracle.sync(x, v, pbest, pbest_loss, losses[s + 1], gbest, np.float32(cfg.w[0]),
+                    np.float32(cfg.c1), np.float32(cfg.c2), cfg.seed, s)
     dt = time.perf_counter() - t0
-    return {"value": cfg.K * n / dt, "unit": "particle-params/s", "cores": 1, "kind": "oracle",
-            "sample": f"one stage, K={cfg.K} x first {n} of {cfg.D} columns of {cfg.name}, "
+    return {"value": stages * cfg.K * n / dt, "unit": "particle-params/s", "cores": 1,
+            "kind": "oracle",
+            "sample": f"{stages} stage(s), K={cfg.K} x first {n} of {cfg.D} columns of {cfg.name}, "
                       f"{dt:.1f} s single-threaded"}
 
 
