@@ -8,7 +8,7 @@
 //   update_kernel        one streaming pass over [K, D]: conditional pbest
 //                        copy, Eq. (6) velocity and Eq. (7) position update.
 // The same two steps exist for K separate row arrays (update_rows_kernel, the
-// gbest copy with a TableSource) and for ragged per-tensor segments, 16 per
+// gbest copy with a TableSource) and for ragged per-tensor segments, 32 per
 // launch (select_gbest_segments_kernel, update_segments_kernel).  Parameter
 // averaging, the synchronization the method replaces, is mean_kernel +
 // broadcast_kernel.
@@ -82,7 +82,7 @@ struct ColumnBlock {
 
 // Row-pointer mode: the K particles are K separate arrays (each worker's own
 // weight tensor); one launch carries at most kTableRows of them by value.
-constexpr int kTableRows = 32;
+constexpr int kTableRows = 64;
 struct RowTable {
     float* x[kTableRows];
     float* v[kTableRows];
@@ -106,7 +106,7 @@ struct MoveParams {
 // keeps its own workgroup order; its workgroups are first_update_wg .. (a
 // multiple of 8, so that wg & 7 is still the XCD) in the update launch and
 // first_copy_wg .. in the gbest copy launch.
-constexpr int kTableSegs = 16;
+constexpr int kTableSegs = 32;
 struct SegEntry {
     float* x;
     float* v;
@@ -286,17 +286,17 @@ __global__ __launch_bounds__(BLOCK) void update_rows_kernel(RowTable tab, const 
 }
 
 // The entry of the segment that workgroup `wg` belongs to (entries are sorted
-// by their first workgroup).  Written as a chain of uniform selects over the
-// by-value table, so that the table stays in scalar registers.
+// by their first workgroup).  The table is a kernel argument: the index is
+// uniform, so the entry is fetched with scalar loads from the argument segment.
 template <bool COPY>
-__device__ __forceinline__ SegEntry segment_of(const SegTable& tab, unsigned wg) {
-    SegEntry e = tab.seg[0];
+__device__ __forceinline__ const SegEntry& segment_of(const SegTable& tab, unsigned wg) {
+    int idx = 0;
 #pragma unroll
     for (int s = 1; s < kTableSegs; ++s) {
         const unsigned first = COPY ? tab.seg[s].first_copy_wg : tab.seg[s].first_update_wg;
-        if (s < tab.count && wg >= first) e = tab.seg[s];
+        if (s < tab.count && wg >= first) idx = s;
     }
-    return e;
+    return tab.seg[idx];
 }
 
 // Update pass over up to kTableSegs ragged segments in one launch.
@@ -304,7 +304,7 @@ template <int BLOCK>
 __global__ __launch_bounds__(BLOCK) void update_segments_kernel(SegTable tab, int K,
                                                                 const Selection* __restrict__ sel,
                                                                 MoveParams m) {
-    const SegEntry e = segment_of<false>(tab, blockIdx.x);
+    const SegEntry& e = segment_of<false>(tab, blockIdx.x);
     unsigned i, tile;
     if (!decode_tile_order(e.ord, (unsigned)K, blockIdx.x - e.first_update_wg, &i, &tile)) return;
     const long long row = (long long)i * e.n;  // segments are dense: row stride = n
@@ -434,7 +434,7 @@ __global__ __launch_bounds__(BLOCK) void select_gbest_segments_kernel(
     } else {
         g = sel->g;
     }
-    const SegEntry e = segment_of<true>(tab, blockIdx.x);
+    const SegEntry& e = segment_of<true>(tab, blockIdx.x);
     const long long c = ((long long)(blockIdx.x - e.first_copy_wg) * BLOCK + threadIdx.x) * 4;
     if (c >= e.n) return;
     const float* src = e.x + (long long)g * e.n;

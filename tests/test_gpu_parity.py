@@ -74,7 +74,7 @@ def test_lenet5_segments_match_flat_and_oracle(oracle):
 @pytest.mark.parametrize("sizes", [
     [5, 0, 1, 1024, 3, 4097, 2, 7],
     # more segments than one launch carries, ResNet-like: many small tensors and a few large ones
-    [64, 64, 1728, 64, 64] * 7 + [0, 36_864, 1, 73_728, 128, 128, 10],
+    [64, 64, 1728, 64, 64] * 14 + [0, 36_864, 1, 73_728, 128, 128, 10],
 ])
 def test_odd_and_empty_segments(oracle, sizes):
     """Segment sizes that are odd (a Philox pair straddles two segments),

@@ -60,13 +60,14 @@ def test_history_trajectory(oracle, K, D, steps):
     (5, 20_000, [0, 0, 0, 0, 0]),              # separately allocated rows, all vector path
     (5, 20_002, [0, 2, 0, 2, 2]),              # some rows 8-byte aligned only
     (4, 9_001, [0, 1, 0, 0]),                  # a 4-byte aligned row: whole launch element-wise
-    (40, 3_000, [0] * 40),                     # two launches of row pointers (32 + 8)
+    (70, 3_000, [0] * 70),                     # two launches of row pointers (64 + 6)
     (33, 1_030, [2 * (i % 2) for i in range(33)]),
+    (65, 1_030, [2 * (i % 2) for i in range(65)]),
 ])
 def test_row_pointer_mode(oracle, K, D, offsets):
     print(f"[case] row pointers K={K} D={D} offsets={offsets[:6]}", flush=True)
     sw = wl.small_swarm(K, D, seed=41 + K, steps=3)
-    if K >= 33:
+    if K >= 65:
         sw.losses[1, K - 1] = 0.01             # g in the second group of rows
     host = [sw.x.copy(), sw.v.copy(), sw.pbest.copy(), sw.pbest_loss.copy(), np.zeros(D, F32)]
     rows = [[gh.to_dev(a[i], offsets[i]) for i in range(K)] for a in (sw.x, sw.v, sw.pbest)]
