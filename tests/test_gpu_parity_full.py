@@ -125,3 +125,96 @@ def test_full_size_per_layer_layout(oracle):
     finally:
         torch.cuda.synchronize()
         pso.pso_ps_destroy(h)
+
+
+def test_full_size_variants(oracle):
+    """Row-pointer mode, historical gBest and parameter averaging at the full
+    benchmark size (K=32, D=25,557,032), each against the oracle on column
+    windows, from one generated swarm."""
+    cfg = wl.CONFIGS["resnet50x32"]
+    K, D = cfg.K, cfg.D
+    print(f"[case] full-size variants: K={K} D={D}", flush=True)
+    sw = wl.make_swarm(cfg, steps=3)
+    wins = windows_of(D)
+    losses, c1, c2, w = sw.losses.copy(), float(sw.c1), float(sw.c2), float(sw.w[0])
+    losses[2] = losses[:2].min() + F32(1.0)          # a stage that keeps the old gbest
+
+    def window_state():
+        return [[np.ascontiguousarray(a[:, lo:hi]) for a in (sw.x, sw.v, sw.pbest)]
+                for lo, hi in wins], [sw.pbest_loss.copy() for _ in wins]
+
+    # -- K separate row arrays ----------------------------------------------------------
+    host, hpl = window_state()
+    xr = [torch.from_numpy(sw.x[i]).to(gh.dev()) for i in range(K)]
+    vr = [torch.from_numpy(sw.v[i]).to(gh.dev()) for i in range(K)]
+    pr = [t.clone() for t in xr]
+    dpl, dg = gh.to_dev(sw.pbest_loss), torch.zeros(D, dtype=torch.float32, device=gh.dev())
+    h = pso.pso_ps_create(K, D)
+    try:
+        for step in range(2):
+            pso.pso_ps_sync_rows(h, xr, vr, pr, dpl, gh.to_dev(losses[step]), dg, w, c1, c2,
+                                 cfg.seed, step)
+            g_dev, imp_dev = pso.pso_ps_last_selection(h, K)
+            for (lo, hi), (hx, hv, hp), pl in zip(wins, host, hpl):
+                hg = np.empty(hi - lo, F32)
+                g, improved = oracle.sync(hx, hv, hp, pl, losses[step], hg, F32(w), F32(c1), F32(c2),
+                                          cfg.seed, step, d0=lo)
+                what = f"rows step {step} columns [{lo},{hi})"
+                assert g_dev == g and imp_dev == [bool(t) for t in improved], what
+                cut = lambda rows: torch.stack([t[lo:hi] for t in rows]).cpu().numpy()
+                gh.assert_bits_equal(dg[lo:hi].cpu().numpy(), hg, what + ": gbest")
+                gh.assert_bits_equal(cut(pr), hp, what + ": pbest")
+                gh.assert_close(cut(xr), hx, what + ": x")
+                gh.assert_close(cut(vr), hv, what + ": v")
+            print(f"[case] rows step {step} ok", flush=True)
+    finally:
+        torch.cuda.synchronize()
+        pso.pso_ps_destroy(h)
+    del xr, vr, pr
+    gc.collect()
+
+    # -- historical gBest on the stacked layout -----------------------------------------
+    host, hpl = window_state()
+    hgb = [np.zeros(hi - lo, F32) for lo, hi in wins]
+    hgl = [np.array([np.inf], F32) for _ in wins]
+    dx, dv = gh.to_dev(sw.x), gh.to_dev(sw.v)
+    dp = dx.clone()
+    dpl, dgl = gh.to_dev(sw.pbest_loss), gh.to_dev(np.array([np.inf], F32))
+    dg.zero_()
+    del sw
+    gc.collect()
+    h = pso.pso_ps_create(K, D)
+    try:
+        kept = 0
+        for step in range(3):
+            pso.pso_ps_sync_history(h, dx, dv, dp, dpl, gh.to_dev(losses[step]), dg, dgl, w, c1, c2,
+                                    cfg.seed, step)
+            g_dev, imp_dev, rep_dev = pso.pso_ps_last_selection(h, K, with_replaced=True)
+            for (lo, hi), (hx, hv, hp), pl, hg, gl in zip(wins, host, hpl, hgb, hgl):
+                g, improved, rep = oracle.sync(hx, hv, hp, pl, losses[step], hg, F32(w), F32(c1),
+                                               F32(c2), cfg.seed, step, d0=lo, gbest_loss=gl)
+                what = f"history step {step} columns [{lo},{hi})"
+                assert (g_dev, imp_dev, rep_dev) == (g, [bool(t) for t in improved], rep), what
+                gh.assert_bits_equal(dgl.cpu().numpy(), gl, what + ": gbest_loss")
+                gh.assert_bits_equal(dg[lo:hi].cpu().numpy(), hg, what + ": gbest")
+                gh.assert_bits_equal(dp[:, lo:hi].cpu().numpy(), hp, what + ": pbest")
+                gh.assert_close(dx[:, lo:hi].cpu().numpy(), hx, what + ": x")
+                gh.assert_close(dv[:, lo:hi].cpu().numpy(), hv, what + ": v")
+            kept += not rep_dev
+            print(f"[case] history step {step} ok (replaced={rep_dev})", flush=True)
+        assert kept == 1
+
+        # -- parameter averaging of the positions just produced -----------------------------
+        dmean = torch.zeros(D, dtype=torch.float32, device=gh.dev())
+        before = [dx[:, lo:hi].cpu().numpy() for lo, hi in wins]
+        pso.pso_ps_average(h, dx, dmean)
+        for (lo, hi), hx in zip(wins, before):
+            hmean = np.empty(hi - lo, F32)
+            oracle.average(hx, hmean)
+            gh.assert_bits_equal(dmean[lo:hi].cpu().numpy(), hmean, f"mean columns [{lo},{hi})")
+            gh.assert_bits_equal(dx[:, lo:hi].cpu().numpy(), hx, f"averaged rows [{lo},{hi})")
+        assert all(torch.equal(dx[i].view(torch.int32), dmean.view(torch.int32)) for i in range(K))
+        print("[case] averaging ok", flush=True)
+    finally:
+        torch.cuda.synchronize()
+        pso.pso_ps_destroy(h)
