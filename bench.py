@@ -126,6 +126,7 @@ def main() -> int:
     ap.add_argument("--block", type=int, default=0, help="threads per workgroup (0 = default)")
     ap.add_argument("--super-tiles", type=int, default=0)
     ap.add_argument("--chunk-tiles", type=int, default=0)
+    ap.add_argument("--wgs-per-cu", type=int, default=0)
     ap.add_argument("--variant", default="sync", choices=["sync", "history", "rows", "segments", "average"],
                     help="sync: the stage (default, the headline); history: historical gBest; "
                          "rows: K separate per-worker arrays; segments: one [K, n] array per "
@@ -181,8 +182,9 @@ def main() -> int:
 
     h = pso.pso_ps_create(K, D, D, seg_sizes=list(cfg.segments)) if args.variant == "segments" \
         else pso.pso_ps_create(K, D)
-    if args.block or args.super_tiles or args.chunk_tiles:
-        pso.pso_ps_set_launch(h, args.block, args.super_tiles, args.chunk_tiles, False)
+    if args.block or args.super_tiles or args.chunk_tiles or args.wgs_per_cu:
+        pso.pso_ps_set_launch(h, args.block, args.super_tiles, args.chunk_tiles, args.wgs_per_cu,
+                              False)
     stream = torch.cuda.current_stream()
 
     def stage(s, ev=None):

@@ -178,9 +178,13 @@ int pso_ps_last_selection(pso_ps_ctx* h, int* g_out, uint64_t* improved_mask_out
  *                  it moves on; bounds the gbest footprint in that XCD's L2
  *   chunk_tiles    consecutive tiles (power of two <= super_tiles) handed to
  *                  one XCD at a time
+ *   wgs_per_cu     cap on the update workgroups resident on one compute unit
+ *                  (>= 3; 64 and above mean no cap), enforced by reserving LDS
+ *                  that the kernel never touches; the default keeps about 20
+ *                  wavefronts per compute unit
  *   force_generic  != 0: element-wise path even where 128-bit accesses are possible */
 int pso_ps_set_launch(pso_ps_ctx* h, int block_threads, int super_tiles, int chunk_tiles,
-                      int force_generic);
+                      int wgs_per_cu, int force_generic);
 
 /* hipError_t (as int) of the last failed HIP call on this handle, 0 if none. */
 int pso_ps_last_hip_error(const pso_ps_ctx* h);

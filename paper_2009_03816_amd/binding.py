@@ -61,7 +61,7 @@ def load():
     lib.pso_ps_inertia.restype = F
     lib.pso_ps_schedule.argtypes = [I64, I64, I64, I64, F, F, F, F, ctypes.POINTER(I),
                                     ctypes.POINTER(F), ctypes.POINTER(F), ctypes.POINTER(F)]
-    lib.pso_ps_set_launch.argtypes = [P, I, I, I, I]
+    lib.pso_ps_set_launch.argtypes = [P, I, I, I, I, I]
     lib.pso_ps_last_hip_error.argtypes = [P]
     lib.pso_ps_destroy.argtypes = [P]
     lib.pso_ps_strerror.argtypes = [I]
@@ -196,9 +196,9 @@ def pso_ps_schedule(t: int, iteration_size: int, epoch_size: int, step: int, m_m
 
 
 def pso_ps_set_launch(h: int, block_threads: int = 0, super_tiles: int = 0, chunk_tiles: int = 0,
-                      force_generic: bool = False) -> None:
-    _check(load().pso_ps_set_launch(h, block_threads, super_tiles, chunk_tiles, int(force_generic)),
-           "pso_ps_set_launch", h)
+                      wgs_per_cu: int = 0, force_generic: bool = False) -> None:
+    _check(load().pso_ps_set_launch(h, block_threads, super_tiles, chunk_tiles, wgs_per_cu,
+                                    int(force_generic)), "pso_ps_set_launch", h)
 
 
 def pso_ps_last_hip_error(h: int) -> int:

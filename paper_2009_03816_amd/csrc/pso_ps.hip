@@ -35,7 +35,10 @@
 //     tiles for row 0, 1, .., K-1 before moving on, so that a gbest tile is
 //     re-read from the XCD's own L2 and the DRAM pages of few rows are open at
 //     a time;
-//   * the Philox rounds are placed between the loads and their first use.
+//   * the Philox rounds are placed between the loads and their first use;
+//   * each launch reserves LDS it never touches, which caps a compute unit at
+//     about 20 resident wavefronts of the 32 it could hold: HBM serves fewer,
+//     steadier request streams better than the full house.
 // Because gbest is copied out by the first kernel, the in-place update of row g
 // cannot race with anything.
 //
@@ -521,6 +524,7 @@ struct pso_ps_ctx {
     int block_threads;     // 0 = default
     int super_tiles;       // 0 = default; else a power of two
     int chunk_tiles;       // 0 = default; else a power of two <= super_tiles
+    int wgs_per_cu;        // 0 = default; else cap on resident update workgroups per compute unit
     bool force_generic;
     bool eight_xcds;       // 256 compute units: the chip is driven as one device of 8 XCDs
     int last_hip_error;
@@ -533,6 +537,7 @@ constexpr int kDefaultBlock = 128;
 constexpr unsigned kDefaultSuperBytes = 2u << 20;    // gbest footprint per XCD, in its 4 MiB L2
 constexpr unsigned kDefaultChunkBytes = 256u << 10;  // consecutive addresses handed to one XCD
 constexpr int kCopyBlock = 256;                      // select_gbest_kernel, average_kernel
+constexpr int kDefaultWavesPerCu = 20;               // resident wavefronts per compute unit (of 32)
 
 // Makes the handle's device current for the lifetime of the object.
 struct DeviceScope {
@@ -604,6 +609,20 @@ bool plan_order(const pso_ps_ctx* h, int rows, unsigned long long tiles, unsigne
     return plan_tile_order(rows, tiles, super, chunk, h->super_tiles != 0, ord, grid);
 }
 
+// Dynamic LDS requested for a streaming launch.  The kernels never touch it:
+// the reservation only caps how many workgroups a compute unit holds at once
+// (160 KiB of LDS per compute unit), which is what the memory system likes.
+unsigned occupancy_cap_lds(const pso_ps_ctx* h, int block) {
+    int wgs = h->wgs_per_cu;
+    if (wgs == 0) {  // default: about kDefaultWavesPerCu wavefronts (sweep: 16-20 of 32 is best)
+        wgs = (kDefaultWavesPerCu * 64 + block - 1) / block;
+        if (wgs < 3) wgs = 3;
+    }
+    if (wgs >= 64) return 0;                              // no cap
+    const unsigned bytes = (160u * 1024u / (unsigned)wgs) & ~511u;
+    return bytes > 64u * 1024u ? 64u * 1024u : bytes;     // default dynamic-LDS limit of a kernel
+}
+
 // Tiles per row: with the vector path tiles are aligned to each row's address.
 template <class RowX>
 unsigned long long tiles_per_row(int rows, long long n, bool vec, unsigned tile, RowX row_x) {
@@ -625,12 +644,13 @@ hipError_t launch_update(const pso_ps_ctx* h, const ColumnBlock& b, const MovePa
     const unsigned long long tiles = tiles_per_row(
         h->K, b.n, vec, BLOCK * 4u, [&](int i) { return b.x + (long long)i * b.ld; });
     if (!plan_order(h, h->K, tiles, BLOCK * 4u, &ord, &grid)) return hipErrorInvalidConfiguration;
+    const unsigned lds = occupancy_cap_lds(h, BLOCK);
     if (vec)
-        hipLaunchKernelGGL((update_kernel<BLOCK, true>), dim3((unsigned)grid), dim3(BLOCK), 0, stream,
-                           b, h->K, (const Selection*)h->sel, m, ord, gbest_loss);
+        hipLaunchKernelGGL((update_kernel<BLOCK, true>), dim3((unsigned)grid), dim3(BLOCK), lds,
+                           stream, b, h->K, (const Selection*)h->sel, m, ord, gbest_loss);
     else
-        hipLaunchKernelGGL((update_kernel<BLOCK, false>), dim3((unsigned)grid), dim3(BLOCK), 0, stream,
-                           b, h->K, (const Selection*)h->sel, m, ord, gbest_loss);
+        hipLaunchKernelGGL((update_kernel<BLOCK, false>), dim3((unsigned)grid), dim3(BLOCK), lds,
+                           stream, b, h->K, (const Selection*)h->sel, m, ord, gbest_loss);
     return hipGetLastError();
 }
 
@@ -644,11 +664,12 @@ hipError_t launch_update_rows(const pso_ps_ctx* h, const RowTable& tab, const fl
     const unsigned long long tiles =
         tiles_per_row(rows, n, vec, BLOCK * 4u, [&](int i) { return tab.x[i]; });
     if (!plan_order(h, rows, tiles, BLOCK * 4u, &ord, &grid)) return hipErrorInvalidConfiguration;
+    const unsigned lds = occupancy_cap_lds(h, BLOCK);
     if (vec)
-        hipLaunchKernelGGL((update_rows_kernel<BLOCK, true>), dim3((unsigned)grid), dim3(BLOCK), 0,
+        hipLaunchKernelGGL((update_rows_kernel<BLOCK, true>), dim3((unsigned)grid), dim3(BLOCK), lds,
                            stream, tab, gbest, n, row0, rows, (const Selection*)h->sel, m, ord);
     else
-        hipLaunchKernelGGL((update_rows_kernel<BLOCK, false>), dim3((unsigned)grid), dim3(BLOCK), 0,
+        hipLaunchKernelGGL((update_rows_kernel<BLOCK, false>), dim3((unsigned)grid), dim3(BLOCK), lds,
                            stream, tab, gbest, n, row0, rows, (const Selection*)h->sel, m, ord);
     return hipGetLastError();
 }
@@ -770,7 +791,7 @@ int pso_ps_create(pso_ps_ctx** out, int K, int64_t D, int64_t ld, int n_seg,
     h->mask_words = (K + 63) / 64;
     h->sel_bytes = sizeof(Selection) + (size_t)(h->mask_words - 1) * sizeof(uint64_t);
     h->sel = nullptr; h->last_stream = nullptr; h->have_selection = false;
-    h->block_threads = 0; h->super_tiles = 0; h->chunk_tiles = 0;
+    h->block_threads = 0; h->super_tiles = 0; h->chunk_tiles = 0; h->wgs_per_cu = 0;
     h->force_generic = false; h->eight_xcds = true; h->last_hip_error = 0;
 
     DeviceScope scope(device);
@@ -907,13 +928,14 @@ int pso_ps_sync_segments(pso_ps_ctx* h, float* const* x_seg, float* const* v_seg
     }
     h->last_stream = stream;
     h->have_selection = true;
+    const unsigned seg_lds = occupancy_cap_lds(h, block);
     for (size_t t = 0; t < tables.size(); ++t) {
         switch (block) {
-            case 64: hipLaunchKernelGGL(update_segments_kernel<64>, dim3(update_totals[t]), dim3(64), 0, stream, tables[t], h->K, (const Selection*)h->sel, m); break;
-            case 128: hipLaunchKernelGGL(update_segments_kernel<128>, dim3(update_totals[t]), dim3(128), 0, stream, tables[t], h->K, (const Selection*)h->sel, m); break;
-            case 256: hipLaunchKernelGGL(update_segments_kernel<256>, dim3(update_totals[t]), dim3(256), 0, stream, tables[t], h->K, (const Selection*)h->sel, m); break;
-            case 512: hipLaunchKernelGGL(update_segments_kernel<512>, dim3(update_totals[t]), dim3(512), 0, stream, tables[t], h->K, (const Selection*)h->sel, m); break;
-            case 1024: hipLaunchKernelGGL(update_segments_kernel<1024>, dim3(update_totals[t]), dim3(1024), 0, stream, tables[t], h->K, (const Selection*)h->sel, m); break;
+            case 64: hipLaunchKernelGGL(update_segments_kernel<64>, dim3(update_totals[t]), dim3(64), seg_lds, stream, tables[t], h->K, (const Selection*)h->sel, m); break;
+            case 128: hipLaunchKernelGGL(update_segments_kernel<128>, dim3(update_totals[t]), dim3(128), seg_lds, stream, tables[t], h->K, (const Selection*)h->sel, m); break;
+            case 256: hipLaunchKernelGGL(update_segments_kernel<256>, dim3(update_totals[t]), dim3(256), seg_lds, stream, tables[t], h->K, (const Selection*)h->sel, m); break;
+            case 512: hipLaunchKernelGGL(update_segments_kernel<512>, dim3(update_totals[t]), dim3(512), seg_lds, stream, tables[t], h->K, (const Selection*)h->sel, m); break;
+            case 1024: hipLaunchKernelGGL(update_segments_kernel<1024>, dim3(update_totals[t]), dim3(1024), seg_lds, stream, tables[t], h->K, (const Selection*)h->sel, m); break;
             default: return PSO_PS_EINVAL;
         }
         const hipError_t e = hipGetLastError();
@@ -986,11 +1008,12 @@ int pso_ps_average(pso_ps_ctx* h, float* x, float* mean, void* hip_stream) {
         tiles_per_row(h->K, n, vec, BLOCK * 4u, [&](int i) { return x + (long long)i * ld; });
     if (!plan_order(h, h->K, tiles, BLOCK * 4u, &ord, &grid))
         return hip_fail(h, hipErrorInvalidConfiguration);
+    const unsigned lds = occupancy_cap_lds(h, BLOCK);
     if (vec)
-        hipLaunchKernelGGL((broadcast_kernel<BLOCK, true>), dim3((unsigned)grid), dim3(BLOCK), 0,
+        hipLaunchKernelGGL((broadcast_kernel<BLOCK, true>), dim3((unsigned)grid), dim3(BLOCK), lds,
                            stream, x, (const float*)mean, ld, n, h->K, ord);
     else
-        hipLaunchKernelGGL((broadcast_kernel<BLOCK, false>), dim3((unsigned)grid), dim3(BLOCK), 0,
+        hipLaunchKernelGGL((broadcast_kernel<BLOCK, false>), dim3((unsigned)grid), dim3(BLOCK), lds,
                            stream, x, (const float*)mean, ld, n, h->K, ord);
     e = hipGetLastError();
     return e == hipSuccess ? PSO_PS_OK : hip_fail(h, e);
@@ -1042,7 +1065,7 @@ int pso_ps_last_selection(pso_ps_ctx* h, int* g_out, uint64_t* improved_mask_out
 }
 
 int pso_ps_set_launch(pso_ps_ctx* h, int block_threads, int super_tiles, int chunk_tiles,
-                      int force_generic) {
+                      int wgs_per_cu, int force_generic) {
     if (!h) return PSO_PS_EINVAL;
     switch (block_threads) {
         case 0: case 64: case 128: case 256: case 512: case 1024: break;
@@ -1050,9 +1073,11 @@ int pso_ps_set_launch(pso_ps_ctx* h, int block_threads, int super_tiles, int chu
     }
     if (super_tiles != 0 && (!is_pow2(super_tiles) || super_tiles > (1 << 20))) return PSO_PS_EINVAL;
     if (chunk_tiles != 0 && (!is_pow2(chunk_tiles) || chunk_tiles > (1 << 20))) return PSO_PS_EINVAL;
+    if (wgs_per_cu < 0 || (wgs_per_cu > 0 && wgs_per_cu < 3)) return PSO_PS_EINVAL;
     h->block_threads = block_threads;
     h->super_tiles = super_tiles;
     h->chunk_tiles = chunk_tiles;
+    h->wgs_per_cu = wgs_per_cu;
     h->force_generic = force_generic != 0;
     return PSO_PS_OK;
 }

@@ -54,7 +54,7 @@ class Pair:
     the oracle."""
 
     def __init__(self, sw, offset: int = 0, block_threads: int = 0, super_tiles: int = 0,
-                 chunk_tiles: int = 0, force_generic: bool = False):
+                 chunk_tiles: int = 0, wgs_per_cu: int = 0, force_generic: bool = False):
         self.sw, self.K, self.D, self.ld = sw, sw.cfg.K, sw.cfg.D, sw.ld
         self.hx, self.hv, self.hp = sw.x.copy(), sw.v.copy(), sw.pbest.copy()
         self.hpl = sw.pbest_loss.copy()
@@ -63,8 +63,9 @@ class Pair:
         self.dpl = to_dev(sw.pbest_loss)
         self.dg = torch.zeros(self.D + offset, dtype=torch.float32, device=dev())[offset:]
         self.h = pso.pso_ps_create(self.K, self.D, self.ld)
-        if block_threads or super_tiles or chunk_tiles or force_generic:
-            pso.pso_ps_set_launch(self.h, block_threads, super_tiles, chunk_tiles, force_generic)
+        if block_threads or super_tiles or chunk_tiles or wgs_per_cu or force_generic:
+            pso.pso_ps_set_launch(self.h, block_threads, super_tiles, chunk_tiles, wgs_per_cu,
+                                  force_generic)
 
     def close(self):
         torch.cuda.synchronize()

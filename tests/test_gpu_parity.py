@@ -122,16 +122,18 @@ def test_shapes_and_alignments(oracle, K, D, ld, offset):
     run_trajectory(oracle, sw, steps=3, offset=offset)
 
 
-@pytest.mark.parametrize("block,sup,chunk,generic", [
-    (64, 0, 0, False), (128, 0, 0, False), (512, 0, 0, False), (1024, 0, 0, False),
-    (64, 0, 0, True), (256, 0, 0, True),
-    (64, 2, 1, False), (64, 4, 4, False), (64, 8, 2, False), (128, 16, 16, False),   # XCD-aware orders
-    (256, 1, 1, False), (64, 32, 8, True)])
-def test_launch_shape_does_not_change_bits(oracle, block, sup, chunk, generic):
-    print(f"[case] block={block} super={sup} chunk={chunk} generic={generic}", flush=True)
+@pytest.mark.parametrize("block,sup,chunk,wgs,generic", [
+    (64, 0, 0, 0, False), (128, 0, 0, 0, False), (512, 0, 0, 0, False), (1024, 0, 0, 0, False),
+    (64, 0, 0, 0, True), (256, 0, 0, 0, True),
+    (64, 2, 1, 0, False), (64, 4, 4, 0, False), (64, 8, 2, 0, False), (128, 16, 16, 0, False),
+    (256, 1, 1, 0, False), (64, 32, 8, 0, True),                         # XCD-aware orders
+    (128, 0, 0, 3, False), (64, 0, 0, 8, False), (1024, 8, 2, 4, False), (256, 0, 0, 100, True)])
+def test_launch_shape_does_not_change_bits(oracle, block, sup, chunk, wgs, generic):
+    print(f"[case] block={block} super={sup} chunk={chunk} wgs_per_cu={wgs} generic={generic}",
+          flush=True)
     sw = wl.small_swarm(9, 70_002, seed=5, steps=2)
     run_trajectory(oracle, sw, steps=2, block_threads=block, super_tiles=sup, chunk_tiles=chunk,
-                   force_generic=generic)
+                   wgs_per_cu=wgs, force_generic=generic)
 
 
 def test_ties_nan_and_inf_losses(oracle):
@@ -183,7 +185,7 @@ def test_random_shapes_alignments_and_layouts(oracle):
             dpl = gh.to_dev(hpl)
             h = pso.pso_ps_create(K, D, D, seg_sizes=sizes)
             try:
-                pso.pso_ps_set_launch(h, block, sup, chunk, False)
+                pso.pso_ps_set_launch(h, block, sup, chunk, 0, False)
                 for s in range(2):
                     pso.pso_ps_sync_segments(h, dx, dv, dp, dpl, gh.to_dev(sw.losses[s]), dg,
                                              0.7, 1.5, 1.5, seed, s)
@@ -413,7 +415,7 @@ def test_error_codes():
     with pytest.raises(pso.PsoPsError) as e:      # flat handle has no segment table
         pso.pso_ps_sync_segments(h, [ok], [ok], [ok], ok, ok, [ok], 0.5, 1.0, 1.0, 0, 0)
     assert e.value.code == pso.PSO_PS_EINVAL
-    for bad in [(100, 0, 0), (256, 3, 0), (256, 0, 6)]:
+    for bad in [(100, 0, 0), (256, 3, 0), (256, 0, 6), (256, 0, 0, 2), (256, 0, 0, -1)]:
         with pytest.raises(pso.PsoPsError):
             pso.pso_ps_set_launch(h, *bad)
     torch.cuda.synchronize()
