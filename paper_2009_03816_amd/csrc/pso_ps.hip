@@ -124,6 +124,10 @@ struct SegEntry {
     int reserved;
 };
 struct SegTable {
+    // The first workgroups again, side by side: the lookup scans them with two
+    // wide scalar loads instead of touching every entry.
+    unsigned first_update_wg[kTableSegs];
+    unsigned first_copy_wg[kTableSegs];
     SegEntry seg[kTableSegs];
     int count;
 };
@@ -296,7 +300,7 @@ __device__ __forceinline__ const SegEntry& segment_of(const SegTable& tab, unsig
     int idx = 0;
 #pragma unroll
     for (int s = 1; s < kTableSegs; ++s) {
-        const unsigned first = COPY ? tab.seg[s].first_copy_wg : tab.seg[s].first_update_wg;
+        const unsigned first = COPY ? tab.first_copy_wg[s] : tab.first_update_wg[s];
         if (s < tab.count && wg >= first) idx = s;
     }
     return tab.seg[idx];
@@ -605,8 +609,8 @@ bool plan_order(const pso_ps_ctx* h, int rows, unsigned long long tiles, unsigne
     // a partitioned device (fewer compute units behind one device) fall back to
     // plain row-major order unless the caller has chosen a shape.
     if (!h->eight_xcds && !h->super_tiles && !h->chunk_tiles)
-        return plan_tile_order(rows, tiles, 1ull << 30, 1, false, ord, grid);
-    return plan_tile_order(rows, tiles, super, chunk, h->super_tiles != 0, ord, grid);
+        return plan_tile_order(rows, tiles, 1ull << 30, 1, ord, grid);
+    return plan_tile_order(rows, tiles, super, chunk, ord, grid);
 }
 
 // Dynamic LDS requested for a streaming launch.  The kernels never touch it:
@@ -896,6 +900,8 @@ int pso_ps_sync_segments(pso_ps_ctx* h, float* const* x_seg, float* const* v_seg
             SegEntry& e = tab.seg[s];
             if (s >= tab.count) {
                 e = tab.seg[tab.count - 1];  // never selected: segment_of stops at count
+                tab.first_update_wg[s] = 0xffffffffu;
+                tab.first_copy_wg[s] = 0xffffffffu;
                 continue;
             }
             const ColumnBlock& b = blocks[first + s];
@@ -910,6 +916,8 @@ int pso_ps_sync_segments(pso_ps_ctx* h, float* const* x_seg, float* const* v_seg
                 return hip_fail(h, hipErrorInvalidConfiguration);
             e.first_update_wg = (unsigned)update_wg;
             e.first_copy_wg = (unsigned)copy_wg;
+            tab.first_update_wg[s] = e.first_update_wg;
+            tab.first_copy_wg[s] = e.first_copy_wg;
             update_wg += grid;
             copy_wg += (unsigned long long)((b.n + 4LL * kCopyBlock - 1) / (4LL * kCopyBlock));
             if (update_wg >= (1ull << 31) || copy_wg >= (1ull << 31))
