@@ -455,11 +455,15 @@ __global__ __launch_bounds__(BLOCK) void select_gbest_segments_kernel(
 // Parameter averaging (Section II-B, step 5) on the stacked layout, first half:
 // one thread owns four columns, sums the K rows in order and divides by K.
 // Reading K rows at one column is tolerant of the rows' different alignments.
+// Column tiles are dealt to the XCDs in chunks like those of the update pass
+// (`ord` is an order for a single row of column tiles).
 template <int BLOCK>
 __global__ __launch_bounds__(BLOCK) void mean_kernel(const float* __restrict__ x,
                                                      float* __restrict__ mean, long long ld,
-                                                     long long n, int K) {
-    const long long c = ((long long)blockIdx.x * BLOCK + threadIdx.x) * 4;
+                                                     long long n, int K, TileOrder ord) {
+    unsigned row, tile;
+    if (!decode_tile_order(ord, 1u, blockIdx.x, &row, &tile)) return;
+    const long long c = ((long long)tile * BLOCK + threadIdx.x) * 4;
     if (c >= n) return;
     const float kf = (float)K;
     if (c + 4 <= n) {
@@ -1001,9 +1005,12 @@ int pso_ps_average(pso_ps_ctx* h, float* x, float* mean, void* hip_stream) {
     const long long n = (long long)h->D;
     const long long ld = (long long)h->ld;
     const long long blocks = (n + 4LL * kCopyBlock - 1) / (4LL * kCopyBlock);
-    if (blocks > 0x7fffffffLL) return hip_fail(h, hipErrorInvalidConfiguration);
-    hipLaunchKernelGGL(mean_kernel<kCopyBlock>, dim3((unsigned)blocks), dim3(kCopyBlock), 0, stream,
-                       (const float*)x, mean, ld, n, h->K);
+    TileOrder mean_ord;
+    unsigned long long mean_grid = 0;
+    if (!plan_order(h, 1, (unsigned long long)blocks, kCopyBlock * 4u, &mean_ord, &mean_grid))
+        return hip_fail(h, hipErrorInvalidConfiguration);
+    hipLaunchKernelGGL(mean_kernel<kCopyBlock>, dim3((unsigned)mean_grid), dim3(kCopyBlock), 0,
+                       stream, (const float*)x, mean, ld, n, h->K, mean_ord);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(h, e);
     // Tiles are aligned to each row's own address, so any 4-byte aligned row
