@@ -218,3 +218,53 @@ def test_full_size_variants(oracle):
     finally:
         torch.cuda.synchronize()
         pso.pso_ps_destroy(h)
+
+
+def test_rows_longer_than_2_to_31_columns(oracle):
+    """Maximum sizes: two rows of 2^31 + 5,242,886 columns each (8.6 GB per row),
+    so that column indices, byte offsets and the flat coordinate of the random
+    numbers all pass 32 bits.  Inputs are drawn on the device (seeded); the
+    oracle advances windows at the start, across column 2^30 (byte offset 2^32),
+    across column 2^31, and at the ragged end."""
+    K, D = 2, (1 << 31) + 5 * (1 << 20) + 6
+    seed, c1, c2, w = 11, 1.3, 1.6, 0.6
+    print(f"[case] long rows: K={K} D={D}", flush=True)
+    gen = torch.Generator(device=gh.dev())
+    gen.manual_seed(2031)
+    dx = torch.empty(K, D, dtype=torch.float32, device=gh.dev())
+    dv = torch.empty(K, D, dtype=torch.float32, device=gh.dev())
+    dx.normal_(0.0, 0.02, generator=gen)
+    dv.normal_(0.0, 0.002, generator=gen)
+    dp = dx.clone()
+    dg = torch.zeros(D, dtype=torch.float32, device=gh.dev())
+    wins = [(0, 2500), ((1 << 30) - 1501, (1 << 30) + 1500), ((1 << 31) - 1499, (1 << 31) + 1502),
+            (D - 2503, D)]
+    host = [[t[:, lo:hi].cpu().numpy().copy() for t in (dx, dv, dp)] for lo, hi in wins]
+    hpl = [np.full(K, np.inf, F32) for _ in wins]
+    dpl = gh.to_dev(np.full(K, np.inf, F32))
+    losses = np.array([[0.9, 0.4], [0.7, 0.5], [0.2, 0.6]], F32)   # g = 1, 1, 0; 2, 1, 1 rows improve
+    h = pso.pso_ps_create(K, D)
+    try:
+        for s in range(3):
+            x_old = dx.clone()
+            pso.pso_ps_sync(h, dx, dv, dp, dpl, gh.to_dev(losses[s]), dg, w, c1, c2, seed, s)
+            g_dev, imp_dev = pso.pso_ps_last_selection(h, K)
+            for (lo, hi), (hx, hv, hp), pl in zip(wins, host, hpl):
+                hg = np.empty(hi - lo, F32)
+                g, improved = oracle.sync(hx, hv, hp, pl, losses[s], hg, F32(w), F32(c1), F32(c2),
+                                          seed, s, d0=lo)
+                what = f"long rows step {s} columns [{lo},{hi})"
+                assert g_dev == g and imp_dev == [bool(t) for t in improved], what
+                gh.assert_bits_equal(dg[lo:hi].cpu().numpy(), hg, what + ": gbest")
+                gh.assert_bits_equal(dp[:, lo:hi].cpu().numpy(), hp, what + ": pbest")
+                gh.assert_close(dx[:, lo:hi].cpu().numpy(), hx, what + ": x")
+                gh.assert_close(dv[:, lo:hi].cpu().numpy(), hv, what + ": v")
+            assert torch.equal(dg.view(torch.int32), x_old[g_dev].view(torch.int32)), "gbest != x_g"
+            for i in range(K):          # row by row: keeps the temporaries at one row
+                assert torch.equal(dx[i], x_old[i] + dv[i]), f"row {i}: x' != x + v'"
+                assert bool((dv[i] != 0).any())
+            del x_old
+            print(f"[case] long rows step {s} ok (g={g_dev}, improved={sum(imp_dev)})", flush=True)
+    finally:
+        torch.cuda.synchronize()
+        pso.pso_ps_destroy(h)
