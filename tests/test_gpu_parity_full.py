@@ -74,7 +74,7 @@ def test_full_size_config(oracle, name):
 
 
 def test_full_size_per_layer_layout(oracle):
-    """The large swarm held as 161 per-tensor [K, n] arrays (11 launches' worth
+    """The large swarm held as 161 per-tensor [K, n] arrays (six launches' worth
     of segments): windows of a small, a mid-sized, the largest and the last
     tensors against the oracle, every array against the flat call's properties."""
     cfg = wl.CONFIGS["resnet50x32_layers"]
