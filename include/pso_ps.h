@@ -176,8 +176,9 @@ int pso_ps_last_selection(pso_ps_ctx* h, int* g_out, uint64_t* improved_mask_out
  *                  block_threads*4 consecutive floats of one row
  *   super_tiles    tiles (power of two) that one XCD walks for every row before
  *                  it moves on; bounds the gbest footprint in that XCD's L2
- *   chunk_tiles    consecutive tiles (power of two <= super_tiles) handed to
- *                  one XCD at a time
+ *   chunk_tiles    longest run of consecutive tiles (power of two <=
+ *                  super_tiles) handed to one XCD at a time; what is left of a
+ *                  row after whole rounds of such runs is dealt in shorter ones
  *   wgs_per_cu     cap on the update workgroups resident on one compute unit
  *                  (>= 3; 64 and above mean no cap), enforced by reserving LDS
  *                  that the kernel never touches; the default keeps about 20
