@@ -53,15 +53,18 @@ class Pair:
     """One swarm held twice: on the device for the library, on the host for
     the oracle."""
 
-    def __init__(self, sw, offset: int = 0, block_threads: int = 0, super_tiles: int = 0,
+    def __init__(self, sw, offset=0, block_threads: int = 0, super_tiles: int = 0,
                  chunk_tiles: int = 0, wgs_per_cu: int = 0, force_generic: bool = False):
+        """offset: elements by which every device array is shifted inside its
+        allocation, or four of them for x, v, pbest and gbest."""
         self.sw, self.K, self.D, self.ld = sw, sw.cfg.K, sw.cfg.D, sw.ld
         self.hx, self.hv, self.hp = sw.x.copy(), sw.v.copy(), sw.pbest.copy()
         self.hpl = sw.pbest_loss.copy()
         self.hg = np.zeros(self.D, F32)
-        self.dx, self.dv, self.dp = (to_dev(a, offset) for a in (sw.x, sw.v, sw.pbest))
+        offs = (offset,) * 4 if isinstance(offset, int) else tuple(offset)
+        self.dx, self.dv, self.dp = (to_dev(a, o) for a, o in zip((sw.x, sw.v, sw.pbest), offs))
         self.dpl = to_dev(sw.pbest_loss)
-        self.dg = torch.zeros(self.D + offset, dtype=torch.float32, device=dev())[offset:]
+        self.dg = torch.zeros(self.D + offs[3], dtype=torch.float32, device=dev())[offs[3]:]
         self.h = pso.pso_ps_create(self.K, self.D, self.ld)
         if block_threads or super_tiles or chunk_tiles or wgs_per_cu or force_generic:
             pso.pso_ps_set_launch(self.h, block_threads, super_tiles, chunk_tiles, wgs_per_cu,
@@ -95,3 +98,73 @@ class Pair:
         assert_bits_equal(self.dp.cpu().numpy(), self.hp, f"{what}: pbest")   # padding included
         assert_close(self.dx.cpu().numpy(), self.hx, f"{what}: x")
         assert_close(self.dv.cpu().numpy(), self.hv, f"{what}: v")
+
+
+# ---------------------------------------------------------------------------
+# Whole arrays at the full benchmark sizes
+# ---------------------------------------------------------------------------
+def host_threads() -> int:
+    import os
+    return max(1, min(16, len(os.sched_getaffinity(0))))
+
+
+def oracle_sync_whole(oracle, x, v, pbest, pbest_loss, loss, gbest, w, c1, c2, seed, step,
+                      gbest_loss=None, d0: int = 0):
+    """One oracle stage over ALL columns of a large swarm: the oracle's own
+    single-threaded routine, called on disjoint column ranges from a thread
+    pool (ctypes releases the GIL).  The update of a column never looks at
+    another column and the random numbers are indexed by the flat coordinate
+    (d0 = first column of the range), so this is the single-threaded result
+    bit for bit; each range gets its own copy of the per-particle scalars,
+    which every range updates identically.  Returns what oracle.sync returns."""
+    from concurrent.futures import ThreadPoolExecutor
+    n = x.shape[1]
+    threads = host_threads()
+    bounds = [n * t // threads for t in range(threads + 1)]
+    loss = np.ascontiguousarray(loss, dtype=F32)
+    pls = [pbest_loss.copy() for _ in range(threads)]
+    gls = [None if gbest_loss is None else gbest_loss.copy() for _ in range(threads)]
+
+    def work(t):
+        lo, hi = bounds[t], bounds[t + 1]
+        if hi == lo:
+            return None
+        return oracle.sync(x[:, lo:hi], v[:, lo:hi], pbest[:, lo:hi], pls[t], loss, gbest[lo:hi],
+                           F32(w), F32(c1), F32(c2), seed, step, d0=d0 + lo, gbest_loss=gls[t])
+
+    with ThreadPoolExecutor(threads) as pool:
+        results = [r for r in pool.map(work, range(threads)) if r is not None]
+    first = results[0]
+    for r in results[1:]:
+        assert r[0] == first[0] and np.array_equal(r[1], first[1]) and r[2:] == first[2:]
+    used = [t for t in range(threads) if bounds[t + 1] > bounds[t]]
+    for t in used[1:]:
+        assert np.array_equal(bits(pls[t]), bits(pls[used[0]]))
+    pbest_loss[:] = pls[used[0]]
+    if gbest_loss is not None:
+        gbest_loss[:] = gls[used[0]]
+    return first
+
+
+def assert_rows_match(dev_rows, host: np.ndarray, what: str, close: bool = False):
+    """Every element of a device array (a [K, n] tensor, a list of K row
+    tensors, or a 1-D tensor) against the oracle's host array.  The host rows
+    are uploaded one at a time and compared on the device; a row that differs
+    is downloaded and reported element-wise.  close: also state the 1e-6
+    relative bar of x and v explicitly (bit equality of finite values implies it)."""
+    if isinstance(dev_rows, torch.Tensor) and dev_rows.dim() == 1:
+        dev_rows, host = [dev_rows], host.reshape(1, -1)
+    for i in range(host.shape[0]):
+        d = dev_rows[i]
+        ref = torch.from_numpy(np.ascontiguousarray(host[i])).to(d.device)
+        same = torch.equal(d.view(torch.int32), ref.view(torch.int32))
+        if close:
+            lim = REL_TOL * torch.maximum(d.abs(), ref.abs())
+            within = bool(((d - ref).abs() <= lim).all())        # false for any NaN
+            if not within:
+                assert_close(d.cpu().numpy(), host[i], f"{what} row {i}")
+                raise AssertionError(f"{what} row {i}: beyond {REL_TOL} relative")
+        if not same:
+            assert_bits_equal(d.cpu().numpy(), host[i], f"{what} row {i}")
+            raise AssertionError(f"{what} row {i}: bits differ")
+        del ref
