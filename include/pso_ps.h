@@ -36,13 +36,13 @@
  *       v = acc; x = x + acc.
  *
  * Memory: every array argument is DEVICE memory owned by the caller, float32,
- * 4-byte aligned (otherwise PSO_PS_EALIGN).  128-bit accesses are used when
- * x, v and pbest are congruent modulo 16 bytes, the row stride is even (or
- * K = 1) and x is 8-byte aligned (for a segment: its address/4 plus its first
- * flat index is even); anything else is accepted and takes a slower
- * element-wise path with identical results.  x, v, pbest, pbest_loss are
- * updated in place; gbest is written; loss is read.  The arrays must not
- * overlap each other.  Padding columns D..ld-1 are neither read nor written.
+ * 4-byte aligned (otherwise PSO_PS_EALIGN).  Any such arrays, row strides and
+ * segment starts take the same 128-bit path (accesses are aligned to each
+ * row's own address in x; v and pbest are fastest when they are congruent to
+ * x modulo 16 bytes); results never depend on alignment.  x, v, pbest,
+ * pbest_loss are updated in place; gbest is written; loss is read.  The
+ * arrays must not overlap each other.  Padding columns D..ld-1 are neither
+ * read nor written.
  *
  * Execution: the calls enqueue work on `hip_stream` (a hipStream_t passed as
  * void*, NULL = the default stream) and return without waiting; nothing is
@@ -115,6 +115,14 @@ int pso_ps_sync_history(pso_ps_ctx* h, float* x, float* v, float* pbest,
                         float* gbest_loss, float w, float c1, float c2,
                         uint64_t seed, uint64_t step, void* hip_stream);
 
+/* pso_ps_sync_segments with the historical global best (see
+ * pso_ps_sync_history): gbest_seg[s] (device [seg_sizes[s]]) and gbest_loss
+ * (device, 1 float) are in/out and persist across stages. */
+int pso_ps_sync_segments_history(pso_ps_ctx* h, float* const* x_seg, float* const* v_seg,
+                                 float* const* pbest_seg, float* pbest_loss, const float* loss,
+                                 float* const* gbest_seg, float* gbest_loss, float w, float c1,
+                                 float c2, uint64_t seed, uint64_t step, void* hip_stream);
+
 /* The stage on K separate per-worker arrays instead of one stacked buffer: the
  * single-GPU stand-in for Algorithm 3's gather and Algorithm 1's "distribute
  * new weights", with no packing copy.  x_rows, v_rows, pbest_rows are HOST
@@ -124,6 +132,13 @@ int pso_ps_sync_rows(pso_ps_ctx* h, float* const* x_rows, float* const* v_rows,
                      float* const* pbest_rows, float* pbest_loss, const float* loss,
                      float* gbest, float w, float c1, float c2,
                      uint64_t seed, uint64_t step, void* hip_stream);
+
+/* pso_ps_sync_rows with the historical global best (see pso_ps_sync_history):
+ * gbest (device [D]) and gbest_loss (device, 1 float) are in/out and persist. */
+int pso_ps_sync_rows_history(pso_ps_ctx* h, float* const* x_rows, float* const* v_rows,
+                             float* const* pbest_rows, float* pbest_loss, const float* loss,
+                             float* gbest, float* gbest_loss, float w, float c1, float c2,
+                             uint64_t seed, uint64_t step, void* hip_stream);
 
 /* Parameter averaging (Section II-B, step 5), the synchronization PSO-PS
  * replaces, on the same stacked layout: mean[d] = (x[0][d] + ... + x[K-1][d]) / K,
@@ -183,7 +198,9 @@ int pso_ps_last_selection(pso_ps_ctx* h, int* g_out, uint64_t* improved_mask_out
  *                  (>= 3; 64 and above mean no cap), enforced by reserving LDS
  *                  that the kernel never touches; the default keeps about 20
  *                  wavefronts per compute unit
- *   force_generic  != 0: element-wise path even where 128-bit accesses are possible */
+ *   force_generic  != 0: element-wise path instead of the 128-bit one
+ * The gbest copy of a stage has a fixed shape of its own (256 threads, 16 KiB
+ * per workgroup) and follows only the chunk and super-chunk sizes, in bytes. */
 int pso_ps_set_launch(pso_ps_ctx* h, int block_threads, int super_tiles, int chunk_tiles,
                       int wgs_per_cu, int force_generic);
 
@@ -193,6 +210,12 @@ int pso_ps_last_hip_error(const pso_ps_ctx* h);
 /* Free the scratch and the handle.  The caller must have synchronized the
  * streams it used with this handle.  NULL is accepted. */
 int pso_ps_destroy(pso_ps_ctx* h);
+
+/* Hash of the source files this library was compiled from (stamped in by the
+ * build; "unstamped" if it was compiled some other way).  The Python binding
+ * refuses, or rebuilds, a library whose stamp differs from the sources next
+ * to it.  Host function; the string is static. */
+const char* pso_ps_source_hash(void);
 
 /* Static, human-readable text for a status code. */
 const char* pso_ps_strerror(int code);

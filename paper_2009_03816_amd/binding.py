@@ -32,18 +32,43 @@ def library_path() -> str:
     return _build.LIBRARY
 
 
+def _built_from(path: str) -> Optional[str]:
+    """The source hash stamped into the library file at `path`, read from the
+    file's bytes (nothing is loaded or run); None if there is no stamp."""
+    marker = b"pso_ps_source_hash="
+    with open(path, "rb") as f:
+        blob = f.read()
+    at = blob.find(marker)
+    if at < 0:
+        return None
+    return blob[at + len(marker):at + len(marker) + 32].decode("ascii", "replace")
+
+
 def load():
-    """Load the built library; build it first if it has never been built.
-    Raises if it can be neither found nor built: there is no fallback path."""
+    """Load the built library.  It is built first if it has never been built,
+    and rebuilt if it was built from other sources than those on disk now
+    (the build stamps a hash of the sources into it).  Raises if it can be
+    neither found nor built: there is no fallback path."""
     global _lib
     if _lib is not None:
         return _lib
     if not os.path.exists(_build.LIBRARY):
         _build.build_library()
+    elif _built_from(_build.LIBRARY) != _build.source_hash():
+        try:
+            _build.build_library()
+        except Exception as exc:
+            raise RuntimeError(
+                f"{_build.LIBRARY} was built from other sources than those in "
+                f"{os.path.dirname(_build.SOURCE)} and could not be rebuilt: {exc}") from exc
     # torch first: the library then binds to the HIP runtime torch has already
     # loaded, so that torch's streams and allocations are valid in its calls.
     import torch  # noqa: F401
     lib = ctypes.CDLL(_build.LIBRARY)
+    lib.pso_ps_source_hash.argtypes = []
+    lib.pso_ps_source_hash.restype = ctypes.c_char_p
+    if lib.pso_ps_source_hash().decode() != _build.source_hash():
+        raise RuntimeError(f"{_build.LIBRARY} does not match the sources it should be built from")
     P, I, I64, U64, F = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_uint64, ctypes.c_float
     PP = ctypes.POINTER(ctypes.c_void_p)
     lib.pso_ps_create.argtypes = [PP, I, I64, I64, I, ctypes.POINTER(I64), I]
@@ -56,6 +81,10 @@ def load():
     lib.pso_ps_sync_history.argtypes = [P, _f32p, _f32p, _f32p, _f32p, _f32p, _f32p, _f32p,
                                         F, F, F, U64, U64, P]
     lib.pso_ps_sync_rows.argtypes = [P, PP, PP, PP, _f32p, _f32p, _f32p, F, F, F, U64, U64, P]
+    lib.pso_ps_sync_segments_history.argtypes = [P, PP, PP, PP, _f32p, _f32p, PP, _f32p, F, F, F,
+                                                 U64, U64, P]
+    lib.pso_ps_sync_rows_history.argtypes = [P, PP, PP, PP, _f32p, _f32p, _f32p, _f32p, F, F, F,
+                                             U64, U64, P]
     lib.pso_ps_average.argtypes = [P, _f32p, _f32p, P]
     lib.pso_ps_inertia.argtypes = [I64, I64, F, F]
     lib.pso_ps_inertia.restype = F
@@ -68,6 +97,7 @@ def load():
     for name in ("pso_ps_create", "pso_ps_sync", "pso_ps_sync_segments", "pso_ps_select",
                  "pso_ps_update", "pso_ps_last_selection", "pso_ps_set_launch",
                  "pso_ps_sync_history", "pso_ps_sync_rows", "pso_ps_average", "pso_ps_schedule",
+                 "pso_ps_sync_segments_history", "pso_ps_sync_rows_history",
                  "pso_ps_last_hip_error", "pso_ps_destroy"):
         getattr(lib, name).restype = I
     lib.pso_ps_strerror.restype = ctypes.c_char_p
@@ -175,6 +205,25 @@ def pso_ps_sync_rows(h: int, x_rows, v_rows, pbest_rows, pbest_loss, loss, gbest
     _check(rc, "pso_ps_sync_rows", h)
 
 
+def pso_ps_sync_segments_history(h: int, x_seg, v_seg, pbest_seg, pbest_loss, loss, gbest_seg,
+                                 gbest_loss, w: float, c1: float, c2: float, seed: int, step: int,
+                                 stream=None) -> None:
+    rc = load().pso_ps_sync_segments_history(h, _table(x_seg), _table(v_seg), _table(pbest_seg),
+                                             _addr(pbest_loss), _addr(loss), _table(gbest_seg),
+                                             _addr(gbest_loss), w, c1, c2, seed, step,
+                                             _stream(stream))
+    _check(rc, "pso_ps_sync_segments_history", h)
+
+
+def pso_ps_sync_rows_history(h: int, x_rows, v_rows, pbest_rows, pbest_loss, loss, gbest,
+                             gbest_loss, w: float, c1: float, c2: float, seed: int, step: int,
+                             stream=None) -> None:
+    rc = load().pso_ps_sync_rows_history(h, _table(x_rows), _table(v_rows), _table(pbest_rows),
+                                         _addr(pbest_loss), _addr(loss), _addr(gbest),
+                                         _addr(gbest_loss), w, c1, c2, seed, step, _stream(stream))
+    _check(rc, "pso_ps_sync_rows_history", h)
+
+
 def pso_ps_average(h: int, x, mean, stream=None) -> None:
     _check(load().pso_ps_average(h, _addr(x), _addr(mean), _stream(stream)), "pso_ps_average", h)
 
@@ -199,6 +248,11 @@ def pso_ps_set_launch(h: int, block_threads: int = 0, super_tiles: int = 0, chun
                       wgs_per_cu: int = 0, force_generic: bool = False) -> None:
     _check(load().pso_ps_set_launch(h, block_threads, super_tiles, chunk_tiles, wgs_per_cu,
                                     int(force_generic)), "pso_ps_set_launch", h)
+
+
+def pso_ps_source_hash() -> str:
+    """Hash of the sources the loaded library was built from."""
+    return load().pso_ps_source_hash().decode()
 
 
 def pso_ps_last_hip_error(h: int) -> int:

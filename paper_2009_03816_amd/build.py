@@ -1,6 +1,7 @@
 """Compiles csrc/pso_ps.hip into libpso_ps.so (in-tree) with hipcc for gfx950."""
 from __future__ import annotations
 
+import hashlib
 import os
 import shutil
 import subprocess
@@ -28,10 +29,29 @@ def hipcc() -> str:
     return exe
 
 
+def source_files() -> list:
+    """Everything the library is compiled from."""
+    csrc = os.path.dirname(SOURCE)
+    return sorted(os.path.join(csrc, n) for n in os.listdir(csrc)) + \
+        [os.path.join(INCLUDE, "pso_ps.h")]
+
+
+def source_hash() -> str:
+    """Hash of the bytes of the sources as they are on disk now.  The build
+    stamps it into the library (pso_ps_source_hash), so that a library built
+    from other sources can be told apart whatever the file times say."""
+    digest = hashlib.sha256()
+    for path in source_files():
+        with open(path, "rb") as f:
+            digest.update(os.path.basename(path).encode() + b"\0" + f.read() + b"\0")
+    return digest.hexdigest()[:32]
+
+
 def build_library(verbose: bool = False) -> str:
     """Always compiles; returns the path of the shared library."""
     tmp = LIBRARY + ".tmp.%d" % os.getpid()
-    cmd = [hipcc(), *HIPCC_FLAGS, "-I", INCLUDE, "-o", tmp, SOURCE]
+    cmd = [hipcc(), *HIPCC_FLAGS, f'-DPSO_PS_SOURCE_HASH="{source_hash()}"', "-I", INCLUDE,
+           "-o", tmp, SOURCE]
     if verbose:
         print(" ".join(cmd))
     subprocess.run(cmd, check=True)

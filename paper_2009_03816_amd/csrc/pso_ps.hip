@@ -106,9 +106,9 @@ struct MoveParams {
 };
 
 // Ragged mode: up to kTableSegs dense [K, n] segments share one launch.  Each
-// keeps its own workgroup order; its workgroups are first_update_wg .. (a
-// multiple of 8, so that wg & 7 is still the XCD) in the update launch and
-// first_copy_wg .. in the gbest copy launch.
+// keeps its own workgroup order; its workgroups start at first_wg (a multiple
+// of 8, so that wg & 7 is still the XCD).  The update launch and the gbest
+// copy launch carry a table each.
 constexpr int kTableSegs = 32;
 struct SegEntry {
     float* x;
@@ -118,17 +118,27 @@ struct SegEntry {
     long long n;
     unsigned long long d0;
     TileOrder ord;
-    unsigned first_update_wg;
-    unsigned first_copy_wg;
+    unsigned first_wg;
     int vec;
-    int reserved;
 };
 struct SegTable {
-    // The first workgroups again, side by side: the lookup scans them with two
+    // The first workgroups again, side by side: the lookup scans them with
     // wide scalar loads instead of touching every entry.
-    unsigned first_update_wg[kTableSegs];
-    unsigned first_copy_wg[kTableSegs];
+    unsigned first_wg[kTableSegs];
     SegEntry seg[kTableSegs];
+    int count;
+};
+struct CopyEntry {
+    const float* x;  // [K, n], dense
+    float* gbest;
+    long long n;
+    TileOrder ord;   // copy tiles of one row
+    unsigned first_wg;
+    int reserved;
+};
+struct CopyTable {
+    unsigned first_wg[kTableSegs];
+    CopyEntry seg[kTableSegs];
     int count;
 };
 
@@ -200,10 +210,16 @@ __device__ __forceinline__ void move_single(const RowPtrs& r, const float* __res
     r.v[col] = vv;
 }
 
-// Columns c .. c+3 of row i with 128-bit accesses (the addresses are 16-byte
-// aligned in x, v and pbest, and d0 + c is even).  improved (uniform over the
-// workgroup): Algorithm 1 replaced this particle's personal best by its
-// position, so pbest is written instead of read.
+// Columns c .. c+3 of row i with 128-bit accesses.  The address of x + c is
+// 16-byte aligned (tiles are aligned to the row's address); v and pbest are
+// read and written at the same columns and may sit at any 4-byte alignment,
+// which the hardware accepts for multi-dword global accesses.  ODD: the flat
+// index d0 + c of the first column is odd, so the four columns take the second
+// half of one Philox call, all of the next and the first half of a third;
+// otherwise they are two whole calls.  improved (uniform over the workgroup):
+// Algorithm 1 replaced this particle's personal best by its position, so pbest
+// is written instead of read.
+template <bool ODD>
 __device__ __forceinline__ void move_quad(const RowPtrs& r, const float* __restrict__ gbest,
                                           unsigned long long d0, long long c, unsigned i,
                                           bool improved, const MoveParams& m) {
@@ -211,9 +227,9 @@ __device__ __forceinline__ void move_quad(const RowPtrs& r, const float* __restr
     float* vp = r.v + c;
     float* pp = r.pbest + c;
     f32x4 x_old = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(xp));
-    f32x4 v_old = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(vp));
+    f32x4 v_old = __builtin_nontemporal_load(reinterpret_cast<const f32x4_a4*>(vp));
     f32x4 p_old = {0.0f, 0.0f, 0.0f, 0.0f};
-    if (!improved) p_old = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(pp));
+    if (!improved) p_old = __builtin_nontemporal_load(reinterpret_cast<const f32x4_a4*>(pp));
     f32x4 gb = *reinterpret_cast<const f32x4_a4*>(gbest + c);
     __builtin_amdgcn_sched_barrier(0);  // all four loads are issued before anything below
 
@@ -224,25 +240,34 @@ __device__ __forceinline__ void move_quad(const RowPtrs& r, const float* __restr
     const uint32_t pair = (uint32_t)((d0 + (unsigned long long)c) >> 1);
     const Words4 ra = philox4x32_10(pair, i, m.step_lo, m.step_hi, m.key0, m.key1);
     const Words4 rb = philox4x32_10(pair + 1u, i, m.step_lo, m.step_hi, m.key0, m.key1);
-    asm volatile("" : "+v"(x_old), "+v"(v_old), "+v"(p_old), "+v"(gb) : "v"(ra.s0), "v"(rb.s0));
+    Words4 rc = rb;
+    if (ODD) rc = philox4x32_10(pair + 2u, i, m.step_lo, m.step_hi, m.key0, m.key1);
+    asm volatile("" : "+v"(x_old), "+v"(v_old), "+v"(p_old), "+v"(gb)
+                 : "v"(ra.s0), "v"(rb.s0), "v"(rc.s0));
 
     const f32x4 pv = improved ? x_old : p_old;
     float xs[4] = {x_old.x, x_old.y, x_old.z, x_old.w};
     float vs[4] = {v_old.x, v_old.y, v_old.z, v_old.w};
-    move_element(xs[0], vs[0], pv.x, gb.x, ra.s0, ra.s1, m);
-    move_element(xs[1], vs[1], pv.y, gb.y, ra.s2, ra.s3, m);
-    move_element(xs[2], vs[2], pv.z, gb.z, rb.s0, rb.s1, m);
-    move_element(xs[3], vs[3], pv.w, gb.w, rb.s2, rb.s3, m);
+    if (!ODD) {
+        move_element(xs[0], vs[0], pv.x, gb.x, ra.s0, ra.s1, m);
+        move_element(xs[1], vs[1], pv.y, gb.y, ra.s2, ra.s3, m);
+        move_element(xs[2], vs[2], pv.z, gb.z, rb.s0, rb.s1, m);
+        move_element(xs[3], vs[3], pv.w, gb.w, rb.s2, rb.s3, m);
+    } else {
+        move_element(xs[0], vs[0], pv.x, gb.x, ra.s2, ra.s3, m);
+        move_element(xs[1], vs[1], pv.y, gb.y, rb.s0, rb.s1, m);
+        move_element(xs[2], vs[2], pv.z, gb.z, rb.s2, rb.s3, m);
+        move_element(xs[3], vs[3], pv.w, gb.w, rc.s0, rc.s1, m);
+    }
     __builtin_nontemporal_store(f32x4{xs[0], xs[1], xs[2], xs[3]}, reinterpret_cast<f32x4*>(xp));
-    __builtin_nontemporal_store(f32x4{vs[0], vs[1], vs[2], vs[3]}, reinterpret_cast<f32x4*>(vp));
-    if (improved) __builtin_nontemporal_store(x_old, reinterpret_cast<f32x4*>(pp));
+    __builtin_nontemporal_store(f32x4{vs[0], vs[1], vs[2], vs[3]}, reinterpret_cast<f32x4_a4*>(vp));
+    if (improved) __builtin_nontemporal_store(x_old, reinterpret_cast<f32x4_a4*>(pp));
 }
 
-// One row x one tile.  VEC: x, v, pbest of the row are congruent modulo 16
-// bytes and (d0 + element address of x) is even, so that an address-aligned
-// group of four floats is two whole Philox pairs; tiles are then aligned to the
-// address of the row.  Otherwise tiles start at column 0 and everything is
-// element-wise.
+// One row x one tile.  VEC: tiles are aligned to the address of the row's x
+// (any 4-byte aligned row qualifies) and whole groups of four columns go
+// through move_quad; the ragged first and last columns of the row, and
+// everything without VEC (tiles then start at column 0), are element-wise.
 template <int BLOCK, bool VEC>
 __device__ __forceinline__ void update_tile(const RowPtrs& r, const float* __restrict__ gbest,
                                             long long n, unsigned long long d0, unsigned i,
@@ -253,7 +278,12 @@ __device__ __forceinline__ void update_tile(const RowPtrs& r, const float* __res
     const long long c = (long long)tile * TILE - phase + 4 * (long long)threadIdx.x;
     if (c + 4 <= 0 || c >= n) return;
     if (VEC && c >= 0 && c + 4 <= n) {
-        move_quad(r, gbest, d0, c, i, improved, m);
+        // parity of the flat index of every quad of this row (TILE and 4 are even)
+        const bool odd = ((unsigned long long)phase + d0) & 1ull;
+        if (odd)
+            move_quad<true>(r, gbest, d0, c, i, improved, m);
+        else
+            move_quad<false>(r, gbest, d0, c, i, improved, m);
     } else {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -284,7 +314,9 @@ template <int BLOCK, bool VEC>
 __global__ __launch_bounds__(BLOCK) void update_rows_kernel(RowTable tab, const float* gbest,
                                                             long long n, int row0, int rows,
                                                             const Selection* __restrict__ sel,
-                                                            MoveParams m, TileOrder ord) {
+                                                            MoveParams m, TileOrder ord,
+                                                            float* gbest_loss) {
+    if (gbest_loss && blockIdx.x == 0 && threadIdx.x == 0) *gbest_loss = sel->gbest_loss;
     unsigned i, tile;
     if (!decode_tile_order(ord, (unsigned)rows, blockIdx.x, &i, &tile)) return;
     const RowPtrs r{tab.x[i], tab.v[i], tab.pbest[i]};
@@ -295,14 +327,12 @@ __global__ __launch_bounds__(BLOCK) void update_rows_kernel(RowTable tab, const 
 // The entry of the segment that workgroup `wg` belongs to (entries are sorted
 // by their first workgroup).  The table is a kernel argument: the index is
 // uniform, so the entry is fetched with scalar loads from the argument segment.
-template <bool COPY>
-__device__ __forceinline__ const SegEntry& segment_of(const SegTable& tab, unsigned wg) {
+template <class Table>
+__device__ __forceinline__ auto segment_of(const Table& tab, unsigned wg) -> decltype(tab.seg[0])& {
     int idx = 0;
 #pragma unroll
-    for (int s = 1; s < kTableSegs; ++s) {
-        const unsigned first = COPY ? tab.first_copy_wg[s] : tab.first_update_wg[s];
-        if (s < tab.count && wg >= first) idx = s;
-    }
+    for (int s = 1; s < kTableSegs; ++s)
+        if (s < tab.count && wg >= tab.first_wg[s]) idx = s;
     return tab.seg[idx];
 }
 
@@ -310,10 +340,11 @@ __device__ __forceinline__ const SegEntry& segment_of(const SegTable& tab, unsig
 template <int BLOCK>
 __global__ __launch_bounds__(BLOCK) void update_segments_kernel(SegTable tab, int K,
                                                                 const Selection* __restrict__ sel,
-                                                                MoveParams m) {
-    const SegEntry& e = segment_of<false>(tab, blockIdx.x);
+                                                                MoveParams m, float* gbest_loss) {
+    if (gbest_loss && blockIdx.x == 0 && threadIdx.x == 0) *gbest_loss = sel->gbest_loss;
+    const SegEntry& e = segment_of(tab, blockIdx.x);
     unsigned i, tile;
-    if (!decode_tile_order(e.ord, (unsigned)K, blockIdx.x - e.first_update_wg, &i, &tile)) return;
+    if (!decode_tile_order(e.ord, (unsigned)K, blockIdx.x - e.first_wg, &i, &tile)) return;
     const long long row = (long long)i * e.n;  // segments are dense: row stride = n
     const RowPtrs r{e.x + row, e.v + row, e.pbest + row};
     const bool improved = is_improved(sel, (int)i);
@@ -374,82 +405,104 @@ __device__ __forceinline__ void wave_argmin(int K, const float* __restrict__ los
     *g_out = best_i;
 }
 
-// Selection and gbest copy.  With do_select every wavefront finds g on its own;
-// wavefront 0 of workgroup 0 also does the pBest test and publishes g, the
-// improved mask and whether gbest is replaced.  Nobody but that wavefront
-// touches pbest_loss or the scratch, and nobody in this launch reads what it
-// writes, so there is no ordering problem.  Without do_select, g and the
-// replace flag are read from the scratch (later segments / row groups).
+// This stage's selection, found by every wavefront on its own.  Wavefront 0 of
+// workgroup 0 also does the pBest test and publishes g, the improved mask and
+// whether gbest is replaced.  Nobody but that wavefront touches pbest_loss or
+// the scratch, and nobody in this launch reads what it writes, so there is no
+// ordering problem.  Without do_select, g and the replace flag are read from
+// the scratch (later segment groups / row groups of the same stage).
 //
 // gbest_loss == null: gbest = x_g always (Algorithm 3).  Otherwise historical
 // gBest: gbest = x_g only if this stage's lowest loss is strictly below
-// *gbest_loss, which this kernel only reads.
-//
-// In row-pointer mode a launch carries some of the rows by value and copies
-// only if g is one of them.
-template <int BLOCK, class Source>
-__global__ __launch_bounds__(BLOCK) void select_gbest_kernel(int K, const float* __restrict__ loss,
-                                                             float* pbest_loss, Selection* sel,
-                                                             Source source,
-                                                             float* __restrict__ gbest, long long n,
-                                                             const float* gbest_loss,
-                                                             int do_select) {
-    int g;
-    bool replace;
+// *gbest_loss, which this launch only reads.
+__device__ __forceinline__ void select_or_recall(int K, const float* __restrict__ loss,
+                                                 float* pbest_loss, Selection* sel,
+                                                 const float* gbest_loss, int do_select, int* g,
+                                                 bool* replace) {
     if (do_select) {
         const bool publisher = blockIdx.x == 0 && threadIdx.x < 64;
         float best;
-        wave_argmin(K, loss, pbest_loss, sel, publisher, &best, &g);
+        wave_argmin(K, loss, pbest_loss, sel, publisher, &best, g);
         const float kept = gbest_loss ? *gbest_loss : 0.0f;
-        replace = gbest_loss ? (best < kept) : true;
+        *replace = gbest_loss ? (best < kept) : true;
         if (publisher && (threadIdx.x & 63) == 0) {
-            sel->g = g;
-            sel->replaced = replace ? 1 : 0;
-            sel->gbest_loss = replace ? best : kept;
+            sel->g = *g;
+            sel->replaced = *replace ? 1 : 0;
+            sel->gbest_loss = *replace ? best : kept;
         }
     } else {
-        g = sel->g;
-        replace = sel->replaced != 0;
-    }
-    if (!replace) return;
-    const float* src = source.row(g);
-    if (!src) return;
-    const long long c = ((long long)blockIdx.x * BLOCK + threadIdx.x) * 4;
-    if (c >= n) return;
-    if (c + 4 <= n) {
-        *reinterpret_cast<f32x4_a4*>(gbest + c) = *reinterpret_cast<const f32x4_a4*>(src + c);
-    } else {
-        for (long long e = c; e < n; ++e) gbest[e] = src[e];
+        *g = sel->g;
+        *replace = sel->replaced != 0;
     }
 }
 
-// Selection (if do_select) and the gbest copies of up to kTableSegs segments.
-template <int BLOCK>
-__global__ __launch_bounds__(BLOCK) void select_gbest_segments_kernel(
-    int K, const float* __restrict__ loss, float* pbest_loss, Selection* sel, SegTable tab,
-    int do_select) {
-    int g;
-    if (do_select) {
-        const bool publisher = blockIdx.x == 0 && threadIdx.x < 64;
-        float best;
-        wave_argmin(K, loss, pbest_loss, sel, publisher, &best, &g);
-        if (publisher && (threadIdx.x & 63) == 0) {
-            sel->g = g;
-            sel->replaced = 1;
-            sel->gbest_loss = best;
+// gbest[0..n) = src[0..n) for one tile of kCopyTile columns: kCopyQuads
+// 128-bit loads per thread, kCopyBlock quads apart, all issued before the
+// first store.  A copy has no other work to hide its memory latency behind,
+// so it wants many bytes in flight per thread and the whole compute unit
+// (no occupancy cap); plain cached accesses measured faster than non-temporal
+// ones here.  Tiles are aligned to the address of src.
+constexpr int kCopyBlock = 256;
+constexpr int kCopyQuads = 4;
+constexpr unsigned kCopyTile = kCopyBlock * 4 * kCopyQuads;  // 4096 floats = 16 KiB
+
+__device__ __forceinline__ void copy_tile(const float* __restrict__ src, float* __restrict__ gbest,
+                                          long long n, unsigned tile) {
+    const long long phase = (long long)((reinterpret_cast<uintptr_t>(src) >> 2) & (kCopyTile - 1u));
+    const long long c0 = (long long)tile * kCopyTile - phase + 4 * (long long)threadIdx.x;
+    f32x4 val[kCopyQuads];
+    bool whole[kCopyQuads];
+#pragma unroll
+    for (int u = 0; u < kCopyQuads; ++u) {
+        const long long c = c0 + (long long)u * (kCopyBlock * 4);
+        whole[u] = c >= 0 && c + 4 <= n;
+        if (whole[u]) val[u] = *reinterpret_cast<const f32x4*>(src + c);
+    }
+#pragma unroll
+    for (int u = 0; u < kCopyQuads; ++u) {
+        const long long c = c0 + (long long)u * (kCopyBlock * 4);
+        if (whole[u]) {
+            *reinterpret_cast<f32x4_a4*>(gbest + c) = val[u];
+        } else {
+            for (int e = 0; e < 4; ++e)
+                if (c + e >= 0 && c + e < n) gbest[c + e] = src[c + e];
         }
-    } else {
-        g = sel->g;
     }
-    const SegEntry& e = segment_of<true>(tab, blockIdx.x);
-    const long long c = ((long long)(blockIdx.x - e.first_copy_wg) * BLOCK + threadIdx.x) * 4;
-    if (c >= e.n) return;
-    const float* src = e.x + (long long)g * e.n;
-    if (c + 4 <= e.n) {
-        *reinterpret_cast<f32x4_a4*>(e.gbest + c) = *reinterpret_cast<const f32x4_a4*>(src + c);
-    } else {
-        for (long long k = c; k < e.n; ++k) e.gbest[k] = src[k];
-    }
+}
+
+// Selection and gbest copy.  The copy takes its tiles in chunks dealt to the
+// XCDs like those of the update pass (`ord` is an order for a single row of
+// copy tiles), so that the XCD that will re-read a slice of gbest K times is,
+// up to a tile at the chunk borders, the one that writes it.  In row-pointer
+// mode a launch carries some of the rows by value and copies only if g is one
+// of them.
+template <class Source>
+__global__ __launch_bounds__(kCopyBlock) void select_gbest_kernel(
+    int K, const float* __restrict__ loss, float* pbest_loss, Selection* sel, Source source,
+    float* __restrict__ gbest, long long n, const float* gbest_loss, int do_select, TileOrder ord) {
+    int g;
+    bool replace;
+    select_or_recall(K, loss, pbest_loss, sel, gbest_loss, do_select, &g, &replace);
+    if (!replace) return;
+    const float* src = source.row(g);
+    if (!src) return;
+    unsigned row, tile;
+    if (!decode_tile_order(ord, 1u, blockIdx.x, &row, &tile)) return;
+    copy_tile(src, gbest, n, tile);
+}
+
+// Selection (if do_select) and the gbest copies of up to kTableSegs segments.
+__global__ __launch_bounds__(kCopyBlock) void select_gbest_segments_kernel(
+    int K, const float* __restrict__ loss, float* pbest_loss, Selection* sel, CopyTable tab,
+    const float* gbest_loss, int do_select) {
+    int g;
+    bool replace;
+    select_or_recall(K, loss, pbest_loss, sel, gbest_loss, do_select, &g, &replace);
+    if (!replace) return;
+    const CopyEntry& e = segment_of(tab, blockIdx.x);
+    unsigned row, tile;
+    if (!decode_tile_order(e.ord, 1u, blockIdx.x - e.first_wg, &row, &tile)) return;
+    copy_tile(e.x + (long long)g * e.n, e.gbest, e.n, tile);
 }
 
 // Parameter averaging (Section II-B, step 5) on the stacked layout, first half:
@@ -522,6 +575,7 @@ struct pso_ps_ctx {
     // not touch the host heap.
     std::vector<ColumnBlock> seg_blocks;
     std::vector<SegTable> seg_tables;
+    std::vector<CopyTable> seg_copy_tables;
     std::vector<unsigned> seg_update_wgs, seg_copy_wgs;
     int device;
     Selection* sel;        // device
@@ -544,7 +598,6 @@ namespace {
 constexpr int kDefaultBlock = 128;
 constexpr unsigned kDefaultSuperBytes = 2u << 20;    // gbest footprint per XCD, in its 4 MiB L2
 constexpr unsigned kDefaultChunkBytes = 256u << 10;  // consecutive addresses handed to one XCD
-constexpr int kCopyBlock = 256;                      // select_gbest_kernel, average_kernel
 constexpr int kDefaultWavesPerCu = 20;               // resident wavefronts per compute unit (of 32)
 
 // Makes the handle's device current for the lifetime of the object.
@@ -585,21 +638,11 @@ int check_block(const ColumnBlock& b) {
     return PSO_PS_OK;
 }
 
-// Can one row take the 128-bit path?  x, v, pbest congruent modulo 16 bytes and
-// (element address of x + flat index of its first column) even.
-bool row_vector_ok(const float* x, const float* v, const float* pbest, unsigned long long d0) {
-    const uintptr_t ax = reinterpret_cast<uintptr_t>(x);
-    const uintptr_t av = reinterpret_cast<uintptr_t>(v);
-    const uintptr_t ap = reinterpret_cast<uintptr_t>(pbest);
-    if (((ax ^ av) & 15u) || ((ax ^ ap) & 15u)) return false;
-    return (((ax >> 2) + d0) & 1ull) == 0;
-}
-
-bool block_vector_ok(const pso_ps_ctx* h, const ColumnBlock& b) {
-    if (h->force_generic) return false;
-    if (h->K > 1 && (b.ld & 1)) return false;
-    return row_vector_ok(b.x, b.v, b.pbest, b.d0);
-}
+// Every 4-byte aligned row can take the 128-bit path (tiles are aligned to the
+// row's own address, v and pbest may be off by any multiple of 4 bytes, the
+// Philox parity of a row is found on the device); the element-wise path is
+// only taken on request.
+bool vector_path(const pso_ps_ctx* h) { return !h->force_generic; }
 
 // Workgroup order for `rows` rows of `tiles` tiles of `tile` floats, with the
 // handle's launch settings.  Returns false if the grid would be too large.
@@ -631,11 +674,13 @@ unsigned occupancy_cap_lds(const pso_ps_ctx* h, int block) {
     return bytes > 64u * 1024u ? 64u * 1024u : bytes;     // default dynamic-LDS limit of a kernel
 }
 
-// Tiles per row: with the vector path tiles are aligned to each row's address.
+// Tiles per row when tiles are aligned to each row's address: enough for the
+// row that starts furthest into a tile.
 template <class RowX>
-unsigned long long tiles_per_row(int rows, long long n, bool vec, unsigned tile, RowX row_x) {
+unsigned long long tiles_per_row(int rows, long long n, bool aligned_to_rows, unsigned tile,
+                                 RowX row_x) {
     unsigned long long max_phase = 0;
-    if (vec) {
+    if (aligned_to_rows) {
         for (int i = 0; i < rows; ++i) {
             const unsigned long long a = (reinterpret_cast<uintptr_t>(row_x(i)) >> 2) & (tile - 1u);
             if (a > max_phase) max_phase = a;
@@ -644,9 +689,22 @@ unsigned long long tiles_per_row(int rows, long long n, bool vec, unsigned tile,
     return (max_phase + (unsigned long long)n + tile - 1) / tile;
 }
 
+int block_of(const pso_ps_ctx* h) { return h->block_threads ? h->block_threads : kDefaultBlock; }
+
+#define PSO_PS_DISPATCH_BLOCK(h, e, CALL)   \
+    switch (block_of(h)) {                  \
+        case 64: e = CALL(64); break;       \
+        case 128: e = CALL(128); break;     \
+        case 256: e = CALL(256); break;     \
+        case 512: e = CALL(512); break;     \
+        case 1024: e = CALL(1024); break;   \
+        default: return PSO_PS_EINVAL;      \
+    }
+
 template <int BLOCK>
-hipError_t launch_update(const pso_ps_ctx* h, const ColumnBlock& b, const MoveParams& m, bool vec,
+hipError_t launch_update(const pso_ps_ctx* h, const ColumnBlock& b, const MoveParams& m,
                          float* gbest_loss, hipStream_t stream) {
+    const bool vec = vector_path(h);
     TileOrder ord;
     unsigned long long grid = 0;
     const unsigned long long tiles = tiles_per_row(
@@ -664,8 +722,9 @@ hipError_t launch_update(const pso_ps_ctx* h, const ColumnBlock& b, const MovePa
 
 template <int BLOCK>
 hipError_t launch_update_rows(const pso_ps_ctx* h, const RowTable& tab, const float* gbest,
-                              int row0, int rows, const MoveParams& m, bool vec,
+                              int row0, int rows, const MoveParams& m, float* gbest_loss,
                               hipStream_t stream) {
+    const bool vec = vector_path(h);
     TileOrder ord;
     unsigned long long grid = 0;
     const long long n = (long long)h->D;
@@ -675,63 +734,69 @@ hipError_t launch_update_rows(const pso_ps_ctx* h, const RowTable& tab, const fl
     const unsigned lds = occupancy_cap_lds(h, BLOCK);
     if (vec)
         hipLaunchKernelGGL((update_rows_kernel<BLOCK, true>), dim3((unsigned)grid), dim3(BLOCK), lds,
-                           stream, tab, gbest, n, row0, rows, (const Selection*)h->sel, m, ord);
+                           stream, tab, gbest, n, row0, rows, (const Selection*)h->sel, m, ord,
+                           gbest_loss);
     else
         hipLaunchKernelGGL((update_rows_kernel<BLOCK, false>), dim3((unsigned)grid), dim3(BLOCK), lds,
-                           stream, tab, gbest, n, row0, rows, (const Selection*)h->sel, m, ord);
+                           stream, tab, gbest, n, row0, rows, (const Selection*)h->sel, m, ord,
+                           gbest_loss);
     return hipGetLastError();
 }
 
-#define PSO_PS_DISPATCH_BLOCK(h, e, CALL)                              \
-    switch ((h)->block_threads ? (h)->block_threads : kDefaultBlock) { \
-        case 64: e = CALL(64); break;                                  \
-        case 128: e = CALL(128); break;                                \
-        case 256: e = CALL(256); break;                                \
-        case 512: e = CALL(512); break;                                \
-        case 1024: e = CALL(1024); break;                              \
-        default: return PSO_PS_EINVAL;                                 \
-    }
+// Order of the gbest copy over `tiles` copy tiles of one row: chunks of the same
+// bytes as the update pass's, whatever its tile size.
+bool plan_copy_order(const pso_ps_ctx* h, unsigned long long tiles, TileOrder* ord,
+                     unsigned long long* grid) {
+    if (!h->eight_xcds) return plan_tile_order(1, tiles, 1ull << 30, 1, ord, grid);
+    const unsigned long long update_tile = (unsigned long long)block_of(h) * 16u;  // bytes
+    unsigned long long super = h->super_tiles ? h->super_tiles * update_tile : kDefaultSuperBytes;
+    unsigned long long chunk = h->chunk_tiles ? h->chunk_tiles * update_tile : kDefaultChunkBytes;
+    super /= kCopyTile * 4ull;
+    chunk /= kCopyTile * 4ull;
+    unsigned long long super2 = 1, chunk2 = 1;  // the planner wants powers of two
+    while (super2 * 2 <= super) super2 *= 2;
+    while (chunk2 * 2 <= chunk) chunk2 *= 2;
+    return plan_tile_order(1, tiles, super2, chunk2, ord, grid);
+}
+
+// Selection (if do_select) and the gbest copy from `source`, whose `rows` rows
+// start at row_x(0..rows-1).
+template <class Source, class RowX>
+int enqueue_select_gbest(pso_ps_ctx* h, float* pbest_loss, const float* loss, const Source& source,
+                         int rows, RowX row_x, float* gbest, long long n, const float* gbest_loss,
+                         bool do_select, hipStream_t stream) {
+    TileOrder ord;
+    unsigned long long grid = 0;
+    const unsigned long long tiles = tiles_per_row(rows, n, true, kCopyTile, row_x);
+    if (!plan_copy_order(h, tiles, &ord, &grid)) return hip_fail(h, hipErrorInvalidConfiguration);
+    hipLaunchKernelGGL((select_gbest_kernel<Source>), dim3((unsigned)grid), dim3(kCopyBlock), 0,
+                       stream, h->K, loss, pbest_loss, h->sel, source, gbest, n, gbest_loss,
+                       do_select ? 1 : 0, ord);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(h, e);
+    h->last_stream = stream;
+    if (do_select) h->have_selection = true;
+    return PSO_PS_OK;
+}
 
 // Enqueue the update pass over one dense block (already validated).
 int enqueue_update(pso_ps_ctx* h, const ColumnBlock& b, const MoveParams& m, float* gbest_loss,
                    hipStream_t stream) {
     if (b.n == 0) return PSO_PS_OK;
-    const bool vec = block_vector_ok(h, b);
     hipError_t e;
-#define CALL(B) launch_update<B>(h, b, m, vec, gbest_loss, stream)
+#define CALL(B) launch_update<B>(h, b, m, gbest_loss, stream)
     PSO_PS_DISPATCH_BLOCK(h, e, CALL)
 #undef CALL
     return e == hipSuccess ? PSO_PS_OK : hip_fail(h, e);
 }
 
 int enqueue_update_rows(pso_ps_ctx* h, const RowTable& tab, const float* gbest, int row0, int rows,
-                        const MoveParams& m, hipStream_t stream) {
-    bool vec = !h->force_generic;
-    for (int i = 0; i < rows && vec; ++i) vec = row_vector_ok(tab.x[i], tab.v[i], tab.pbest[i], 0);
+                        const MoveParams& m, float* gbest_loss, hipStream_t stream) {
     hipError_t e;
-#define CALL(B) launch_update_rows<B>(h, tab, gbest, row0, rows, m, vec, stream)
+#define CALL(B) launch_update_rows<B>(h, tab, gbest, row0, rows, m, gbest_loss, stream)
     PSO_PS_DISPATCH_BLOCK(h, e, CALL)
 #undef CALL
     return e == hipSuccess ? PSO_PS_OK : hip_fail(h, e);
-}
-
-// Enqueue selection (if do_select) and the gbest copy from `source`.
-template <class Source>
-int enqueue_select_gbest(pso_ps_ctx* h, float* pbest_loss, const float* loss, const Source& source,
-                         float* gbest, long long n, const float* gbest_loss, bool do_select,
-                         hipStream_t stream) {
-    if (n == 0 && !do_select) return PSO_PS_OK;
-    long long blocks = (n + 4LL * kCopyBlock - 1) / (4LL * kCopyBlock);
-    if (blocks < 1) blocks = 1;  // selection still has to run
-    if (blocks > 0x7fffffffLL) return hip_fail(h, hipErrorInvalidConfiguration);
-    hipLaunchKernelGGL((select_gbest_kernel<kCopyBlock, Source>), dim3((unsigned)blocks),
-                       dim3(kCopyBlock), 0, stream, h->K, loss, pbest_loss, h->sel, source, gbest,
-                       n, gbest_loss, do_select ? 1 : 0);
-    const hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return hip_fail(h, e);
-    h->last_stream = stream;
-    if (do_select) h->have_selection = true;
-    return PSO_PS_OK;
 }
 
 MoveParams make_params(float w, float c1, float c2, uint64_t seed, uint64_t step) {
@@ -755,10 +820,159 @@ int sync_flat(pso_ps_ctx* h, float* x, float* v, float* pbest, float* pbest_loss
     if (rc != PSO_PS_OK) return rc;
     DeviceScope scope(h->device);
     if (scope.err != hipSuccess) return hip_fail(h, scope.err);
-    rc = enqueue_select_gbest(h, pbest_loss, loss, StackedSource{x, b.ld}, gbest, b.n, gbest_loss,
-                              true, stream);
+    rc = enqueue_select_gbest(h, pbest_loss, loss, StackedSource{x, b.ld}, h->K,
+                              [&](int i) { return x + (long long)i * b.ld; }, gbest, b.n,
+                              gbest_loss, true, stream);
     if (rc != PSO_PS_OK) return rc;
     return enqueue_update(h, b, m, gbest_loss, stream);
+}
+
+// The ragged stage; gbest_loss as in sync_flat.
+int sync_segments(pso_ps_ctx* h, float* const* x_seg, float* const* v_seg, float* const* pbest_seg,
+                  float* pbest_loss, const float* loss, float* const* gbest_seg, float* gbest_loss,
+                  const MoveParams& m, hipStream_t stream) {
+    if (!h || !x_seg || !v_seg || !pbest_seg || !gbest_seg || !pbest_loss || !loss)
+        return PSO_PS_EINVAL;
+    if (h->seg_sizes.empty()) return PSO_PS_EINVAL;
+    if (!aligned_to(pbest_loss, 4) || !aligned_to(loss, 4) || !aligned_to(gbest_loss, 4))
+        return PSO_PS_EALIGN;
+    const int n_seg = (int)h->seg_sizes.size();
+    // Validate every segment before anything is enqueued.  The work lists were
+    // reserved at create: no allocation happens here.
+    std::vector<ColumnBlock>& blocks = h->seg_blocks;
+    std::vector<SegTable>& tables = h->seg_tables;
+    std::vector<CopyTable>& copy_tables = h->seg_copy_tables;
+    std::vector<unsigned>& update_totals = h->seg_update_wgs;
+    std::vector<unsigned>& copy_totals = h->seg_copy_wgs;
+    blocks.clear(); tables.clear(); copy_tables.clear(); update_totals.clear(); copy_totals.clear();
+    unsigned long long start = 0;
+    for (int s = 0; s < n_seg; ++s) {
+        const long long n = (long long)h->seg_sizes[s];
+        if (n > 0) {
+            ColumnBlock b{x_seg[s], v_seg[s], pbest_seg[s], gbest_seg[s], n, n, start};
+            const int rc = check_block(b);
+            if (rc != PSO_PS_OK) return rc;
+            blocks.push_back(b);
+        }
+        start += (unsigned long long)n;
+    }
+    DeviceScope scope(h->device);
+    if (scope.err != hipSuccess) return hip_fail(h, scope.err);
+    const int block = block_of(h);
+    const bool vec = vector_path(h);
+    // Up to kTableSegs segments per launch; the selection rides on the first
+    // gbest-copy launch.  All copies are enqueued before the first update.
+    for (size_t first = 0; first < blocks.size(); first += kTableSegs) {
+        SegTable tab;
+        CopyTable ctab;
+        tab.count = (int)((blocks.size() - first < (size_t)kTableSegs) ? blocks.size() - first
+                                                                      : (size_t)kTableSegs);
+        ctab.count = tab.count;
+        unsigned long long update_wg = 0, copy_wg = 0;
+        for (int s = 0; s < kTableSegs; ++s) {
+            SegEntry& e = tab.seg[s];
+            CopyEntry& c = ctab.seg[s];
+            if (s >= tab.count) {
+                e = tab.seg[tab.count - 1];  // never selected: segment_of stops at count
+                c = ctab.seg[tab.count - 1];
+                tab.first_wg[s] = 0xffffffffu;
+                ctab.first_wg[s] = 0xffffffffu;
+                continue;
+            }
+            const ColumnBlock& b = blocks[first + s];
+            const auto row_x = [&](int i) { return b.x + (long long)i * b.ld; };
+            e.x = b.x; e.v = b.v; e.pbest = b.pbest; e.gbest = b.gbest;
+            e.n = b.n; e.d0 = b.d0;
+            e.vec = vec ? 1 : 0;
+            c.x = b.x; c.gbest = b.gbest; c.n = b.n; c.reserved = 0;
+            const unsigned tile = (unsigned)block * 4u;
+            unsigned long long grid = 0, copy_grid = 0;
+            if (!plan_order(h, h->K, tiles_per_row(h->K, b.n, vec, tile, row_x), tile, &e.ord, &grid) ||
+                !plan_copy_order(h, tiles_per_row(h->K, b.n, true, kCopyTile, row_x), &c.ord,
+                                 &copy_grid))
+                return hip_fail(h, hipErrorInvalidConfiguration);
+            e.first_wg = tab.first_wg[s] = (unsigned)update_wg;
+            c.first_wg = ctab.first_wg[s] = (unsigned)copy_wg;
+            update_wg += grid;
+            copy_wg += copy_grid;
+            if (update_wg >= (1ull << 31) || copy_wg >= (1ull << 31))
+                return hip_fail(h, hipErrorInvalidConfiguration);
+        }
+        tables.push_back(tab);
+        copy_tables.push_back(ctab);
+        update_totals.push_back((unsigned)update_wg);
+        copy_totals.push_back((unsigned)copy_wg);
+    }
+    for (size_t t = 0; t < copy_tables.size(); ++t) {
+        hipLaunchKernelGGL(select_gbest_segments_kernel, dim3(copy_totals[t]), dim3(kCopyBlock), 0,
+                           stream, h->K, loss, pbest_loss, h->sel, copy_tables[t],
+                           (const float*)gbest_loss, t == 0 ? 1 : 0);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail(h, e);
+    }
+    h->last_stream = stream;
+    h->have_selection = true;
+    const unsigned lds = occupancy_cap_lds(h, block);
+    for (size_t t = 0; t < tables.size(); ++t) {
+        float* const store_loss = t == 0 ? gbest_loss : nullptr;
+#define PSO_PS_LAUNCH(B)                                                                      \
+    hipLaunchKernelGGL(update_segments_kernel<B>, dim3(update_totals[t]), dim3(B), lds, stream, \
+                       tables[t], h->K, (const Selection*)h->sel, m, store_loss)
+        switch (block) {
+            case 64: PSO_PS_LAUNCH(64); break;
+            case 128: PSO_PS_LAUNCH(128); break;
+            case 256: PSO_PS_LAUNCH(256); break;
+            case 512: PSO_PS_LAUNCH(512); break;
+            case 1024: PSO_PS_LAUNCH(1024); break;
+            default: return PSO_PS_EINVAL;
+        }
+#undef PSO_PS_LAUNCH
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail(h, e);
+    }
+    return PSO_PS_OK;
+}
+
+// The stage on K separate rows; gbest_loss as in sync_flat.
+int sync_rows(pso_ps_ctx* h, float* const* x_rows, float* const* v_rows, float* const* pbest_rows,
+              float* pbest_loss, const float* loss, float* gbest, float* gbest_loss,
+              const MoveParams& m, hipStream_t stream) {
+    if (!h || !x_rows || !v_rows || !pbest_rows || !pbest_loss || !loss || !gbest)
+        return PSO_PS_EINVAL;
+    if (!aligned_to(pbest_loss, 4) || !aligned_to(loss, 4) || !aligned_to(gbest_loss, 4))
+        return PSO_PS_EALIGN;
+    for (int i = 0; i < h->K; ++i) {
+        const int rc = check_arrays(x_rows[i], v_rows[i], pbest_rows[i], gbest);
+        if (rc != PSO_PS_OK) return rc;
+    }
+    DeviceScope scope(h->device);
+    if (scope.err != hipSuccess) return hip_fail(h, scope.err);
+    const long long n = (long long)h->D;
+    // gbest copies first (each launch carries up to kTableRows row pointers and
+    // copies only if g is among them), then the updates.
+    for (int row0 = 0; row0 < h->K; row0 += kTableRows) {
+        TableSource src;
+        src.row0 = row0;
+        src.rows = (h->K - row0 < kTableRows) ? h->K - row0 : kTableRows;
+        for (int i = 0; i < kTableRows; ++i) src.x[i] = (i < src.rows) ? x_rows[row0 + i] : nullptr;
+        const int rc = enqueue_select_gbest(h, pbest_loss, loss, src, src.rows,
+                                            [&](int i) { return x_rows[row0 + i]; }, gbest, n,
+                                            gbest_loss, row0 == 0, stream);
+        if (rc != PSO_PS_OK) return rc;
+    }
+    for (int row0 = 0; row0 < h->K; row0 += kTableRows) {
+        RowTable tab;
+        const int rows = (h->K - row0 < kTableRows) ? h->K - row0 : kTableRows;
+        for (int i = 0; i < kTableRows; ++i) {
+            tab.x[i] = (i < rows) ? x_rows[row0 + i] : nullptr;
+            tab.v[i] = (i < rows) ? v_rows[row0 + i] : nullptr;
+            tab.pbest[i] = (i < rows) ? pbest_rows[row0 + i] : nullptr;
+        }
+        const int rc = enqueue_update_rows(h, tab, gbest, row0, rows, m,
+                                           row0 == 0 ? gbest_loss : nullptr, stream);
+        if (rc != PSO_PS_OK) return rc;
+    }
+    return PSO_PS_OK;
 }
 
 }  // namespace
@@ -789,6 +1003,7 @@ int pso_ps_create(pso_ps_ctx** out, int K, int64_t D, int64_t ld, int n_seg,
             const size_t launches = ((size_t)n_seg + kTableSegs - 1) / kTableSegs;
             h->seg_blocks.reserve((size_t)n_seg);
             h->seg_tables.reserve(launches);
+            h->seg_copy_tables.reserve(launches);
             h->seg_update_wgs.reserve(launches);
             h->seg_copy_wgs.reserve(launches);
         }
@@ -828,7 +1043,9 @@ int pso_ps_select(pso_ps_ctx* h, const float* x, float* pbest_loss, const float*
         return PSO_PS_EALIGN;
     DeviceScope scope(h->device);
     if (scope.err != hipSuccess) return hip_fail(h, scope.err);
-    return enqueue_select_gbest(h, pbest_loss, loss, StackedSource{x, (long long)h->ld}, gbest,
+    const long long ld = (long long)h->ld;
+    return enqueue_select_gbest(h, pbest_loss, loss, StackedSource{x, ld}, h->K,
+                                [&](int i) { return x + (long long)i * ld; }, gbest,
                                 (long long)h->D, nullptr, true, (hipStream_t)hip_stream);
 }
 
@@ -865,135 +1082,33 @@ int pso_ps_sync_segments(pso_ps_ctx* h, float* const* x_seg, float* const* v_seg
                          float* const* pbest_seg, float* pbest_loss, const float* loss,
                          float* const* gbest_seg, float w, float c1, float c2,
                          uint64_t seed, uint64_t step, void* hip_stream) {
-    if (!h || !x_seg || !v_seg || !pbest_seg || !gbest_seg || !pbest_loss || !loss)
-        return PSO_PS_EINVAL;
-    if (h->seg_sizes.empty()) return PSO_PS_EINVAL;
-    if (!aligned_to(pbest_loss, 4) || !aligned_to(loss, 4)) return PSO_PS_EALIGN;
-    const int n_seg = (int)h->seg_sizes.size();
-    // Validate every segment before anything is enqueued.  The work lists were
-    // reserved at create: no allocation happens here.
-    std::vector<ColumnBlock>& blocks = h->seg_blocks;
-    std::vector<SegTable>& tables = h->seg_tables;
-    std::vector<unsigned>& update_totals = h->seg_update_wgs;
-    std::vector<unsigned>& copy_totals = h->seg_copy_wgs;
-    blocks.clear(); tables.clear(); update_totals.clear(); copy_totals.clear();
-    unsigned long long start = 0;
-    for (int s = 0; s < n_seg; ++s) {
-        const long long n = (long long)h->seg_sizes[s];
-        if (n > 0) {
-            ColumnBlock b{x_seg[s], v_seg[s], pbest_seg[s], gbest_seg[s], n, n, start};
-            const int rc = check_block(b);
-            if (rc != PSO_PS_OK) return rc;
-            blocks.push_back(b);
-        }
-        start += (unsigned long long)n;
-    }
-    DeviceScope scope(h->device);
-    if (scope.err != hipSuccess) return hip_fail(h, scope.err);
-    const hipStream_t stream = (hipStream_t)hip_stream;
-    const MoveParams m = make_params(w, c1, c2, seed, step);
-    const int block = h->block_threads ? h->block_threads : kDefaultBlock;
-    // Up to kTableSegs segments per launch; the selection rides on the first
-    // gbest-copy launch.  All copies are enqueued before the first update.
-    for (size_t first = 0; first < blocks.size(); first += kTableSegs) {
-        SegTable tab;
-        tab.count = (int)((blocks.size() - first < (size_t)kTableSegs) ? blocks.size() - first
-                                                                      : (size_t)kTableSegs);
-        unsigned long long update_wg = 0, copy_wg = 0;
-        for (int s = 0; s < kTableSegs; ++s) {
-            SegEntry& e = tab.seg[s];
-            if (s >= tab.count) {
-                e = tab.seg[tab.count - 1];  // never selected: segment_of stops at count
-                tab.first_update_wg[s] = 0xffffffffu;
-                tab.first_copy_wg[s] = 0xffffffffu;
-                continue;
-            }
-            const ColumnBlock& b = blocks[first + s];
-            e.x = b.x; e.v = b.v; e.pbest = b.pbest; e.gbest = b.gbest;
-            e.n = b.n; e.d0 = b.d0; e.reserved = 0;
-            e.vec = block_vector_ok(h, b) ? 1 : 0;
-            const unsigned tile = (unsigned)block * 4u;
-            const unsigned long long tiles = tiles_per_row(
-                h->K, b.n, e.vec != 0, tile, [&](int i) { return b.x + (long long)i * b.ld; });
-            unsigned long long grid = 0;
-            if (!plan_order(h, h->K, tiles, tile, &e.ord, &grid))
-                return hip_fail(h, hipErrorInvalidConfiguration);
-            e.first_update_wg = (unsigned)update_wg;
-            e.first_copy_wg = (unsigned)copy_wg;
-            tab.first_update_wg[s] = e.first_update_wg;
-            tab.first_copy_wg[s] = e.first_copy_wg;
-            update_wg += grid;
-            copy_wg += (unsigned long long)((b.n + 4LL * kCopyBlock - 1) / (4LL * kCopyBlock));
-            if (update_wg >= (1ull << 31) || copy_wg >= (1ull << 31))
-                return hip_fail(h, hipErrorInvalidConfiguration);
-        }
-        tables.push_back(tab);
-        update_totals.push_back((unsigned)update_wg);
-        copy_totals.push_back((unsigned)copy_wg);
-    }
-    for (size_t t = 0; t < tables.size(); ++t) {
-        hipLaunchKernelGGL(select_gbest_segments_kernel<kCopyBlock>, dim3(copy_totals[t]),
-                           dim3(kCopyBlock), 0, stream, h->K, loss, pbest_loss, h->sel, tables[t],
-                           t == 0 ? 1 : 0);
-        const hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return hip_fail(h, e);
-    }
-    h->last_stream = stream;
-    h->have_selection = true;
-    const unsigned seg_lds = occupancy_cap_lds(h, block);
-    for (size_t t = 0; t < tables.size(); ++t) {
-        switch (block) {
-            case 64: hipLaunchKernelGGL(update_segments_kernel<64>, dim3(update_totals[t]), dim3(64), seg_lds, stream, tables[t], h->K, (const Selection*)h->sel, m); break;
-            case 128: hipLaunchKernelGGL(update_segments_kernel<128>, dim3(update_totals[t]), dim3(128), seg_lds, stream, tables[t], h->K, (const Selection*)h->sel, m); break;
-            case 256: hipLaunchKernelGGL(update_segments_kernel<256>, dim3(update_totals[t]), dim3(256), seg_lds, stream, tables[t], h->K, (const Selection*)h->sel, m); break;
-            case 512: hipLaunchKernelGGL(update_segments_kernel<512>, dim3(update_totals[t]), dim3(512), seg_lds, stream, tables[t], h->K, (const Selection*)h->sel, m); break;
-            case 1024: hipLaunchKernelGGL(update_segments_kernel<1024>, dim3(update_totals[t]), dim3(1024), seg_lds, stream, tables[t], h->K, (const Selection*)h->sel, m); break;
-            default: return PSO_PS_EINVAL;
-        }
-        const hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return hip_fail(h, e);
-    }
-    return PSO_PS_OK;
+    return sync_segments(h, x_seg, v_seg, pbest_seg, pbest_loss, loss, gbest_seg, nullptr,
+                         make_params(w, c1, c2, seed, step), (hipStream_t)hip_stream);
+}
+
+int pso_ps_sync_segments_history(pso_ps_ctx* h, float* const* x_seg, float* const* v_seg,
+                                 float* const* pbest_seg, float* pbest_loss, const float* loss,
+                                 float* const* gbest_seg, float* gbest_loss, float w, float c1,
+                                 float c2, uint64_t seed, uint64_t step, void* hip_stream) {
+    if (!gbest_loss) return PSO_PS_EINVAL;
+    return sync_segments(h, x_seg, v_seg, pbest_seg, pbest_loss, loss, gbest_seg, gbest_loss,
+                         make_params(w, c1, c2, seed, step), (hipStream_t)hip_stream);
 }
 
 int pso_ps_sync_rows(pso_ps_ctx* h, float* const* x_rows, float* const* v_rows,
                      float* const* pbest_rows, float* pbest_loss, const float* loss, float* gbest,
                      float w, float c1, float c2, uint64_t seed, uint64_t step, void* hip_stream) {
-    if (!h || !x_rows || !v_rows || !pbest_rows || !pbest_loss || !loss || !gbest)
-        return PSO_PS_EINVAL;
-    if (!aligned_to(pbest_loss, 4) || !aligned_to(loss, 4)) return PSO_PS_EALIGN;
-    for (int i = 0; i < h->K; ++i) {
-        const int rc = check_arrays(x_rows[i], v_rows[i], pbest_rows[i], gbest);
-        if (rc != PSO_PS_OK) return rc;
-    }
-    DeviceScope scope(h->device);
-    if (scope.err != hipSuccess) return hip_fail(h, scope.err);
-    const hipStream_t stream = (hipStream_t)hip_stream;
-    const long long n = (long long)h->D;
-    // gbest copies first (each launch carries up to kTableRows row pointers and
-    // copies only if g is among them), then the updates.
-    for (int row0 = 0; row0 < h->K; row0 += kTableRows) {
-        TableSource src;
-        src.row0 = row0;
-        src.rows = (h->K - row0 < kTableRows) ? h->K - row0 : kTableRows;
-        for (int i = 0; i < kTableRows; ++i) src.x[i] = (i < src.rows) ? x_rows[row0 + i] : nullptr;
-        const int rc = enqueue_select_gbest(h, pbest_loss, loss, src, gbest, n, nullptr, row0 == 0,
-                                            stream);
-        if (rc != PSO_PS_OK) return rc;
-    }
-    const MoveParams m = make_params(w, c1, c2, seed, step);
-    for (int row0 = 0; row0 < h->K; row0 += kTableRows) {
-        RowTable tab;
-        const int rows = (h->K - row0 < kTableRows) ? h->K - row0 : kTableRows;
-        for (int i = 0; i < kTableRows; ++i) {
-            tab.x[i] = (i < rows) ? x_rows[row0 + i] : nullptr;
-            tab.v[i] = (i < rows) ? v_rows[row0 + i] : nullptr;
-            tab.pbest[i] = (i < rows) ? pbest_rows[row0 + i] : nullptr;
-        }
-        const int rc = enqueue_update_rows(h, tab, gbest, row0, rows, m, stream);
-        if (rc != PSO_PS_OK) return rc;
-    }
-    return PSO_PS_OK;
+    return sync_rows(h, x_rows, v_rows, pbest_rows, pbest_loss, loss, gbest, nullptr,
+                     make_params(w, c1, c2, seed, step), (hipStream_t)hip_stream);
+}
+
+int pso_ps_sync_rows_history(pso_ps_ctx* h, float* const* x_rows, float* const* v_rows,
+                             float* const* pbest_rows, float* pbest_loss, const float* loss,
+                             float* gbest, float* gbest_loss, float w, float c1, float c2,
+                             uint64_t seed, uint64_t step, void* hip_stream) {
+    if (!gbest_loss) return PSO_PS_EINVAL;
+    return sync_rows(h, x_rows, v_rows, pbest_rows, pbest_loss, loss, gbest, gbest_loss,
+                     make_params(w, c1, c2, seed, step), (hipStream_t)hip_stream);
 }
 
 int pso_ps_average(pso_ps_ctx* h, float* x, float* mean, void* hip_stream) {
@@ -1108,6 +1223,15 @@ int pso_ps_destroy(pso_ps_ctx* h) {
     }
     delete h;
     return rc;
+}
+
+#ifndef PSO_PS_SOURCE_HASH
+#define PSO_PS_SOURCE_HASH "unstamped"
+#endif
+const char* pso_ps_source_hash(void) {
+    // The marker lets a tool find the stamp in the file without loading it.
+    static const char stamp[] = "pso_ps_source_hash=" PSO_PS_SOURCE_HASH;
+    return stamp + sizeof("pso_ps_source_hash=") - 1;
 }
 
 const char* pso_ps_strerror(int code) {

@@ -59,7 +59,7 @@ def test_history_trajectory(oracle, K, D, steps):
 @pytest.mark.parametrize("K,D,offsets", [
     (5, 20_000, [0, 0, 0, 0, 0]),              # separately allocated rows, all vector path
     (5, 20_002, [0, 2, 0, 2, 2]),              # some rows 8-byte aligned only
-    (4, 9_001, [0, 1, 0, 0]),                  # a 4-byte aligned row: whole launch element-wise
+    (4, 9_001, [0, 1, 0, 3]),                  # 4-byte aligned rows: odd parity of the random pairs
     (70, 3_000, [0] * 70),                     # two launches of row pointers (64 + 6)
     (33, 1_030, [2 * (i % 2) for i in range(33)]),
     (65, 1_030, [2 * (i % 2) for i in range(65)]),
@@ -84,6 +84,83 @@ def test_row_pointer_mode(oracle, K, D, offsets):
             stack = lambda parts: torch.stack(parts)
             dev = [stack(rows[0]), stack(rows[1]), stack(rows[2]), dpl, dg]
             compare_state(dev, host, f"rows K={K} D={D} step {s}")
+    finally:
+        torch.cuda.synchronize()
+        pso.pso_ps_destroy(h)
+
+
+@pytest.mark.parametrize("K,D,offsets", [
+    (5, 20_002, [0, 2, 1, 3, 0]),              # every alignment among the rows
+    (70, 3_001, [i % 4 for i in range(70)]),   # two launches of row pointers, g moves between them
+])
+def test_row_pointer_mode_with_history(oracle, K, D, offsets):
+    print(f"[case] row pointers + historical gBest K={K} D={D}", flush=True)
+    steps = 6
+    sw = wl.small_swarm(K, D, seed=43 + K, steps=steps)
+    losses = sw.losses.copy()
+    losses[1, K - 1] = 0.01                    # g in the last group of rows, a new best
+    losses[2] = losses[:2].min() + F32(0.25)   # cannot replace
+    losses[4, 0] = losses[:4].min()            # ties the best so far: kept
+    host = [sw.x.copy(), sw.v.copy(), sw.pbest.copy(), sw.pbest_loss.copy(), np.full(D, 3.0, F32)]
+    hgl = np.array([np.inf], F32)
+    # v and pbest of a row sit at other alignments than its x
+    rows = [[gh.to_dev(a[i], (offsets[i] + shift) % 4) for i in range(K)]
+            for a, shift in ((sw.x, 0), (sw.v, 1), (sw.pbest, 2))]
+    dpl, dg, dgl = gh.to_dev(sw.pbest_loss), gh.to_dev(host[4]), gh.to_dev(hgl)
+    h = pso.pso_ps_create(K, D)
+    kept = 0
+    try:
+        for s in range(steps):
+            pso.pso_ps_sync_rows_history(h, rows[0], rows[1], rows[2], dpl, gh.to_dev(losses[s]), dg,
+                                         dgl, 0.7, 1.5, 1.5, 7, s)
+            g, improved, rep = oracle.sync(host[0], host[1], host[2], host[3], losses[s], host[4],
+                                           F32(0.7), F32(1.5), F32(1.5), 7, s, gbest_loss=hgl)
+            gg, gi, grep = pso.pso_ps_last_selection(h, K, with_replaced=True)
+            what = f"rows+history K={K} D={D} step {s}"
+            assert (gg, gi, grep) == (g, [bool(t) for t in improved], rep), what
+            gh.assert_bits_equal(dgl.cpu().numpy(), hgl, what + ": gbest_loss")
+            dev = [torch.stack(rows[0]), torch.stack(rows[1]), torch.stack(rows[2]), dpl, dg]
+            compare_state(dev, host, what)
+            kept += not rep
+        assert kept >= 2
+    finally:
+        torch.cuda.synchronize()
+        pso.pso_ps_destroy(h)
+
+
+@pytest.mark.parametrize("sizes", [
+    list(wl.LENET5_SEGMENTS),
+    [64, 63, 1728, 1, 64] * 14 + [0, 36_864, 1, 73_729, 128, 127, 10],   # three launches, odd starts
+])
+def test_segments_with_history(oracle, sizes):
+    K, D, steps = 6, sum(sizes), 6
+    print(f"[case] segments + historical gBest K={K} D={D} in {len(sizes)} segments", flush=True)
+    sw = wl.small_swarm(K, D, seed=47, steps=steps)
+    losses = sw.losses.copy()
+    losses[2] = losses[:2].min() + F32(0.25)   # cannot replace
+    losses[4, 1] = losses[:4].min()            # ties the best so far: kept
+    losses[5] = np.nan                         # nobody wins, nothing improves
+    hx, hv, hp, hpl = sw.x.copy(), sw.v.copy(), sw.pbest.copy(), sw.pbest_loss.copy()
+    hg, hgl = np.full(D, 3.0, F32), np.array([np.inf], F32)
+    dx, dv, dp = ([gh.to_dev(a) for a in wl.segment_views(t, sizes)] for t in (sw.x, sw.v, sw.pbest))
+    dg = [gh.to_dev(a) for a in wl.segment_views(hg, sizes)]
+    dpl, dgl = gh.to_dev(sw.pbest_loss), gh.to_dev(hgl)
+    h = pso.pso_ps_create(K, D, D, seg_sizes=sizes)
+    kept = 0
+    try:
+        for s in range(steps):
+            pso.pso_ps_sync_segments_history(h, dx, dv, dp, dpl, gh.to_dev(losses[s]), dg, dgl,
+                                             0.6, 1.1, 1.4, 47, s)
+            g, improved, rep = oracle.sync(hx, hv, hp, hpl, losses[s], hg, F32(0.6), F32(1.1),
+                                           F32(1.4), 47, s, gbest_loss=hgl)
+            gg, gi, grep = pso.pso_ps_last_selection(h, K, with_replaced=True)
+            what = f"segments+history step {s}"
+            assert (gg, gi, grep) == (g, [bool(t) for t in improved], rep), what
+            gh.assert_bits_equal(dgl.cpu().numpy(), hgl, what + ": gbest_loss")
+            cat = lambda parts: torch.cat(parts, dim=-1)
+            compare_state([cat(dx), cat(dv), cat(dp), dpl, cat(dg)], [hx, hv, hp, hpl, hg], what)
+            kept += not rep
+        assert kept >= 3
     finally:
         torch.cuda.synchronize()
         pso.pso_ps_destroy(h)

@@ -7,10 +7,13 @@
 //    two while it still fits, single tiles at the end;
 //  - an XCD walks the tiles of a row in address order, takes the rows of a tile
 //    in order, and comes back to a tile for the next row after at most one
-//    super-chunk of other work.
+//    super-chunk of other work;
+//  - decoded as a single row (the gbest copy does that), the same order gives
+//    every tile once, on the XCD that owns it in the K-row pass.
 // Built by tests/test_tile_order.py against the library's own header.
 #include <cstdio>
 #include <cstdlib>
+#include <cstring>
 #include <vector>
 
 #include "tile_order.h"
@@ -60,6 +63,24 @@ static int check(int rows, unsigned long long tiles, unsigned long long super, u
     }
     for (unsigned char s : seen)
         if (!s) return 9;  // skipped
+
+    // The gbest copy decodes the order of the K-row pass as a single row: the
+    // plan must not depend on the number of rows, and every tile must come up
+    // once, on the XCD that owns it in the K-row pass.
+    TileOrder one;
+    unsigned long long grid1 = 0;
+    if (!plan_tile_order(1, tiles, super, chunk, &one, &grid1)) return 12;
+    if (std::memcmp(&one, &ord, sizeof ord) != 0 || grid1 * (unsigned long long)rows != grid) return 13;
+    std::vector<unsigned char> seen1((size_t)tiles, 0);
+    for (unsigned long long wg = 0; wg < grid1; ++wg) {
+        unsigned row = ~0u, tile = ~0u;
+        if (!decode_tile_order(ord, 1u, (unsigned)wg, &row, &tile)) continue;
+        if (row != 0 || tile >= tiles || seen1[tile]) return 14;
+        seen1[tile] = 1;
+        if (owner[tile] != (int)(wg & 7u)) return 15;
+    }
+    for (unsigned char s : seen1)
+        if (!s) return 16;
     return 0;
 }
 
