@@ -5,9 +5,10 @@
 
 A step is one whole synchronization stage (selection + fused update) of the
 named swarm, whose state is resident in HBM before the timed region starts.
-Prints ONE JSON line: whole-job particle-parameters per second, the HBM
-roofline of the update kernel measured live with events on the launch stream,
-and the CPU oracle timed on a bounded sample of the same workload.
+Prints ONE JSON line: whole-job particle-parameters per second over the timed
+pso_ps_sync calls, the HBM roofline of the whole stage and of each of its two
+kernels measured live with events on the launch stream, and the CPU oracle
+timed on a bounded sample of the same workload.
 """
 from __future__ import annotations
 
@@ -32,6 +33,13 @@ MEASURED_TRAFFIC = {
     # profiles/update_kernel_resnet50x32_hbm_traffic.md: mean of three timed launches
     ("resnet50x32", "75be0b27336ea88a"): 16460299000.0,
 }
+
+# What plain streams reach on MI355X with the access mix of the update pass
+# (profiles/stream_ceilings_resnet50x32.md); quoted next to the roofline fraction
+# as the practical ceiling under the 8 TB/s peak.  Stored, not measured in this run.
+STREAM_CEILING = {
+    "in_place_3_reads_2_writes_GBps": 6650.0, "read_only_GBps": 7060.0, "copy_1r1w_GBps": 6600.0,
+    "source": "profiles/stream_ceilings_resnet50x32.md (stored figures, another run)"}
 
 
 def kernel_source_hash() -> str:
@@ -117,6 +125,25 @@ def cpu_baseline(cfg, seconds_target: float = 15.0, all_cores: bool = True):
     return out
 
 
+def time_stages(stage, first, count, stream, torch):
+    """Enqueue `count` stages with an event before the first and after each, wait
+    once, and return (wall seconds, per-stage milliseconds)."""
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(count + 1)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    marks[0].record(stream)
+    for k in range(count):
+        stage(first + k)
+        marks[k + 1].record(stream)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    return elapsed, [marks[k].elapsed_time(marks[k + 1]) for k in range(count)]
+
+
+def summary(ms):
+    return {"avg": sum(ms) / len(ms), "median": sorted(ms)[len(ms) // 2], "min": min(ms)}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -127,11 +154,19 @@ def main() -> int:
     ap.add_argument("--super-tiles", type=int, default=0)
     ap.add_argument("--chunk-tiles", type=int, default=0)
     ap.add_argument("--wgs-per-cu", type=int, default=0)
-    ap.add_argument("--variant", default="sync", choices=["sync", "history", "rows", "segments", "average"],
+    ap.add_argument("--force-generic", action="store_true",
+                    help="element-wise path instead of the 128-bit one (a measurement of that path)")
+    ap.add_argument("--misalign", default="",
+                    help="four element offsets 'x,v,pbest,gbest' of the arrays inside their "
+                         "allocations (default: all 0, i.e. 16-byte aligned and congruent)")
+    ap.add_argument("--variant", default="sync",
+                    choices=["sync", "history", "rows", "segments", "average"],
                     help="sync: the stage (default, the headline); history: historical gBest; "
                          "rows: K separate per-worker arrays; segments: one [K, n] array per "
                          "parameter tensor (needs a workload with a segment list); "
                          "average: parameter averaging")
+    ap.add_argument("--graph", action="store_true",
+                    help="sync only: also replay the stages from a HIP graph and report that time")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch one plain device copy of 1 GiB (counter calibration)")
@@ -152,13 +187,21 @@ def main() -> int:
     cfg = wl.CONFIGS[args.workload]
     K, D = cfg.K, cfg.D
     dev = torch.device("cuda:0")
-    total = args.warmup + args.steps
+    total = args.warmup + 2 * args.steps            # the timed pass and the per-kernel pass
+    offs = [int(t) for t in args.misalign.split(",")] if args.misalign else [0, 0, 0, 0]
+
+    def shifted(a, off):
+        """`a` on the device, starting `off` elements into its allocation."""
+        flat = torch.empty(a.size + off, dtype=torch.float32, device=dev)
+        view = flat[off:].view(a.shape)
+        view.copy_(torch.from_numpy(a))
+        return view
 
     sw = wl.make_swarm(cfg, steps=total)
     if args.variant == "rows":                           # K separately allocated arrays
-        xr = [torch.from_numpy(sw.x[i]).to(dev) for i in range(K)]
-        vr = [torch.from_numpy(sw.v[i]).to(dev) for i in range(K)]
-        pr = [t.clone() for t in xr]
+        xr = [shifted(sw.x[i], offs[0]) for i in range(K)]
+        vr = [shifted(sw.v[i], offs[1]) for i in range(K)]
+        pr = [shifted(sw.x[i], offs[2]) for i in range(K)]
         dx = xr[0]
     elif args.variant == "segments":                     # one dense [K, n] array per tensor
         if not cfg.segments:
@@ -170,32 +213,25 @@ def main() -> int:
         gs = [torch.zeros(n, dtype=torch.float32, device=dev) for n in cfg.segments]
         dx = max(xs, key=lambda t: t.numel())
     else:
-        dx = torch.from_numpy(sw.x).to(dev)
-        dv = torch.from_numpy(sw.v).to(dev)
-        dp = dx.clone()
+        dx, dv, dp = shifted(sw.x, offs[0]), shifted(sw.v, offs[1]), shifted(sw.x, offs[2])
     dpl = torch.from_numpy(sw.pbest_loss).to(dev)
     dloss = torch.from_numpy(sw.losses).to(dev)          # [total, K], resident
-    dg = torch.zeros(D, dtype=torch.float32, device=dev)
+    dg = shifted(np.zeros(D, np.float32), offs[3])
     dgl = torch.full((1,), float("inf"), dtype=torch.float32, device=dev)
     w_tab, c1, c2 = [float(t) for t in sw.w], float(sw.c1), float(sw.c2)
     del sw
 
     h = pso.pso_ps_create(K, D, D, seg_sizes=list(cfg.segments)) if args.variant == "segments" \
         else pso.pso_ps_create(K, D)
-    if args.block or args.super_tiles or args.chunk_tiles or args.wgs_per_cu:
+    if args.block or args.super_tiles or args.chunk_tiles or args.wgs_per_cu or args.force_generic:
         pso.pso_ps_set_launch(h, args.block, args.super_tiles, args.chunk_tiles, args.wgs_per_cu,
-                              False)
+                              args.force_generic)
     stream = torch.cuda.current_stream()
 
-    def stage(s, ev=None):
-        # events bracket the dominant kernel where the entry points allow it,
-        # else the whole call (history, rows: selection + update)
+    def stage(s):
+        """One whole synchronization stage through the entry point of the variant."""
         if args.variant == "sync":
-            pso.pso_ps_select(h, dx, dpl, dloss[s], dg, stream)
-        if ev:
-            ev[0].record(stream)
-        if args.variant == "sync":
-            pso.pso_ps_update(h, dx, dv, dp, dg, w_tab[s], c1, c2, cfg.seed, s, stream)
+            pso.pso_ps_sync(h, dx, dv, dp, dpl, dloss[s], dg, w_tab[s], c1, c2, cfg.seed, s, stream)
         elif args.variant == "history":
             pso.pso_ps_sync_history(h, dx, dv, dp, dpl, dloss[s], dg, dgl, w_tab[s], c1, c2,
                                     cfg.seed, s, stream)
@@ -207,39 +243,74 @@ def main() -> int:
                                      cfg.seed, s, stream)
         else:
             pso.pso_ps_average(h, dx, dg, stream)
-        if ev:
-            ev[1].record(stream)
 
+    # -- the timed region: K whole stages through the entry point ---------------------------
     for s in range(args.warmup):
         stage(s)
-    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-              for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for k in range(args.steps):
-        stage(args.warmup + k, events[k])
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
+    elapsed, stage_ms = time_stages(stage, args.warmup, args.steps, stream, torch)
+    stage_t = summary(stage_ms)
 
-    kernel_ms = [a.elapsed_time(b) for a, b in events]
-    avg_ms = sum(kernel_ms) / len(kernel_ms)
-    median_ms = sorted(kernel_ms)[len(kernel_ms) // 2]
-    if args.variant == "average":
-        algo_bytes = 4.0 * D * (2 * K + 1)               # read K rows, write K rows and the mean
-        kernel = "mean_kernel + broadcast_kernel"
-    elif args.variant == "sync":
-        algo_bytes = 4.0 * D * (5 * K + 1)               # per update launch
-        kernel = "update_kernel"
-    else:
-        algo_bytes = 4.0 * D * (5 * K + 3)               # whole call: + read x_g, write gbest
-        kernel = {"rows": "select_gbest_kernel + update_rows_kernel",
-                  "segments": "select_gbest_segments_kernel + update_segments_kernel",
-                  "history": "select_gbest_kernel + update_kernel"}[args.variant]
-    achieved = algo_bytes / (avg_ms * 1e-3) / 1e9
+    # -- a second pass over as many stages, split at the kernel boundary --------------------
+    # (sync only: pso_ps_select + pso_ps_update are the two halves of pso_ps_sync, bit for
+    # bit; an event between them gives each kernel's own duration on the launch stream)
+    select_ms, update_ms = [], []
+    if args.variant == "sync":
+        marks = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+        for k in range(args.steps):
+            s = args.warmup + args.steps + k
+            marks[k][0].record(stream)
+            pso.pso_ps_select(h, dx, dpl, dloss[s], dg, stream)
+            marks[k][1].record(stream)
+            pso.pso_ps_update(h, dx, dv, dp, dg, w_tab[s], c1, c2, cfg.seed, s, stream)
+            marks[k][2].record(stream)
+        torch.cuda.synchronize()
+        select_ms = [m[0].elapsed_time(m[1]) for m in marks]
+        update_ms = [m[1].elapsed_time(m[2]) for m in marks]
     assert bool(torch.isfinite(dx).all()), "state went non-finite"
 
-    # context for the roofline fraction: what a plain device copy of one [K, D]
-    # array reaches on this machine, measured the same way (read + write bytes)
+    # -- optional: the same stages replayed from a HIP graph --------------------------------
+    graph_ms = None
+    if args.graph and args.variant == "sync":
+        per_graph = min(args.steps, 10)
+        side = torch.cuda.Stream()
+        side.wait_stream(stream)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            for k in range(per_graph):
+                s = args.warmup + k
+                pso.pso_ps_sync(h, dx, dv, dp, dpl, dloss[s], dg, w_tab[s], c1, c2, cfg.seed, s,
+                                side)
+        graph.replay()
+        torch.cuda.synchronize()
+        replays = max(1, args.steps // per_graph)
+        ge = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        ge[0].record(stream)
+        for _ in range(replays):
+            graph.replay()
+        ge[1].record(stream)
+        torch.cuda.synchronize()
+        graph_ms = ge[0].elapsed_time(ge[1]) / (replays * per_graph)
+
+    # -- byte counts -------------------------------------------------------------------------
+    if args.variant == "average":
+        stage_bytes = 4.0 * D * (2 * K + 1)              # read K rows, write K rows and the mean
+        kernel = "mean_kernel + broadcast_kernel"
+    else:
+        stage_bytes = 4.0 * D * (5 * K + 1)              # the least a stage can move (see below)
+        kernel = {"sync": "update_kernel", "rows": "select_gbest_kernel + update_rows_kernel",
+                  "segments": "select_gbest_segments_kernel + update_segments_kernel",
+                  "history": "select_gbest_kernel + update_kernel"}[args.variant]
+    stage_gbs = stage_bytes / (stage_t["avg"] * 1e-3) / 1e9
+    stage_roof = {
+        "what": "the whole entry-point call, events around each of the timed stages",
+        "bytes": stage_bytes, "ms_avg": stage_t["avg"], "ms_median": stage_t["median"],
+        "ms_min": stage_t["min"], "achieved": stage_gbs, "frac": stage_gbs / HBM_PEAK_GBS,
+        "bytes_are": "algorithmic minimum 4*D*(5K+1): x, v read and written, pbest read or "
+                     "written, gbest written once; the two-kernel split moves 4*D*(5K+3)"
+        if args.variant != "average" else "4*D*(2K+1)"}
+
+    # context for the fractions: torch's own device-to-device copy of one [K, D] array on
+    # this box (read + write bytes).  It is NOT a ceiling: the library's kernels beat it.
     if args.variant == "rows":
         copy_src, copy_dst = torch.stack(xr), torch.empty(K, D, dtype=torch.float32, device=dev)
     elif args.variant == "segments":
@@ -263,8 +334,43 @@ def main() -> int:
         dst.copy_(src)
         torch.cuda.synchronize()
 
-    traffic = MEASURED_TRAFFIC.get((cfg.name, kernel_source_hash())) if args.variant == "sync" \
-        else None
+    if args.variant == "sync":
+        upd, sel = summary(update_ms), summary(select_ms)
+        kernel_bytes = 4.0 * D * (5 * K + 1)             # per update launch: 20 B per particle
+        achieved = kernel_bytes / (upd["avg"] * 1e-3) / 1e9   # parameter + first read of gbest
+        default_shape = not (args.block or args.super_tiles or args.chunk_tiles or args.wgs_per_cu
+                             or args.force_generic or args.misalign)
+        key = (cfg.name, kernel_source_hash())
+        traffic = MEASURED_TRAFFIC.get(key) if default_shape else None
+        roofline = {
+            "bound": "hbm", "kernel": kernel, "achieved": achieved, "peak": HBM_PEAK_GBS,
+            "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+            "traffic_is": "a stored rocprofv3 --pmc reading (FETCH_SIZE + WRITE_SIZE, "
+                          "profiles/update_kernel_resnet50x32_hbm_traffic.md), valid for the kernel "
+                          "source hash it was taken with; null once the kernels have changed",
+            "kernel_source_hash": key[1],
+            "algorithmic_bytes_per_launch": kernel_bytes,
+            "kernel_ms_avg": upd["avg"], "kernel_ms_median": upd["median"],
+            "kernel_ms_min": upd["min"],
+            "kernel_pass": "a second pass over the same number of stages as pso_ps_select + "
+                           "pso_ps_update with an event between the two kernels",
+            "select_kernel": {"kernel": "select_gbest_kernel", "bytes": 8.0 * D,
+                              "ms_avg": sel["avg"], "ms_median": sel["median"], "ms_min": sel["min"],
+                              "achieved": 8.0 * D / (sel["avg"] * 1e-3) / 1e9,
+                              "frac": 8.0 * D / (sel["avg"] * 1e-3) / 1e9 / HBM_PEAK_GBS},
+            "stage": stage_roof,
+        }
+    else:
+        roofline = {"bound": "hbm", "kernel": kernel, "achieved": stage_gbs, "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": stage_gbs / HBM_PEAK_GBS, "traffic": None,
+                    "algorithmic_bytes_per_launch": stage_bytes, "kernel_ms_avg": stage_t["avg"],
+                    "kernel_ms_median": stage_t["median"], "kernel_ms_min": stage_t["min"],
+                    "stage": stage_roof}
+    roofline["stream_ceiling"] = STREAM_CEILING
+    roofline["torch_copy_GBps_same_box"] = copy_gbs
+    if graph_ms is not None:
+        roofline["stage"]["hip_graph_replay_ms"] = graph_ms
+
     out = {
         "metric": "PSO sync particle-params/s" if args.variant != "average"
         else "parameter-averaging particle-params/s", "value": K * D * args.steps / elapsed,
@@ -273,14 +379,15 @@ def main() -> int:
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: K={K} particles x D={D} fp32 parameters, "
                                f"w={cfg.w[0]}, c1={cfg.c1}, c2={cfg.c2}", "K": K, "D": D,
-                   "variant": args.variant},
-        "roofline": {"bound": "hbm", "kernel": kernel, "achieved": achieved,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": traffic, "algorithmic_bytes_per_launch": algo_bytes,
-                     "kernel_ms_avg": avg_ms, "kernel_ms_median": median_ms,
-                     "kernel_ms_min": min(kernel_ms),
-                     "device_copy_GBps_same_box": copy_gbs},
+                   "variant": args.variant,
+                   "entry_point": {"sync": "pso_ps_sync", "history": "pso_ps_sync_history",
+                                   "rows": "pso_ps_sync_rows", "segments": "pso_ps_sync_segments",
+                                   "average": "pso_ps_average"}[args.variant]},
+        "roofline": roofline,
     }
+    if args.force_generic or args.misalign:
+        out["config"]["path"] = ("element-wise (forced)" if args.force_generic else "128-bit") + \
+            (f", array offsets {offs}" if args.misalign else "")
     torch.cuda.synchronize()
     pso.pso_ps_destroy(h)
     del dx, dg
