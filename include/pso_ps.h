@@ -69,6 +69,9 @@ extern "C" {
 #define PSO_PS_EALIGN  (-2)  /* an array is not 4-byte aligned */
 #define PSO_PS_EHIP    (-3)  /* a HIP runtime call failed; see pso_ps_last_hip_error */
 #define PSO_PS_ENOMEM  (-4)  /* host allocation failed */
+#define PSO_PS_ELIMIT  (-5)  /* pso_ps_sync_static: K beyond PSO_PS_STATIC_MAX_K */
+
+#define PSO_PS_STATIC_MAX_K 4096  /* largest swarm pso_ps_sync_static accepts */
 
 typedef struct pso_ps_ctx pso_ps_ctx;
 
@@ -139,6 +142,25 @@ int pso_ps_sync_rows_history(pso_ps_ctx* h, float* const* x_rows, float* const* 
                              float* const* pbest_rows, float* pbest_loss, const float* loss,
                              float* gbest, float* gbest_loss, float w, float c1, float c2,
                              uint64_t seed, uint64_t step, void* hip_stream);
+
+/* pso_ps_sync for callers that cannot allocate device memory: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  No
+ * handle: the few bytes of selection scratch that pso_ps_create would allocate
+ * live in a fixed device array inside the library (about 768 bytes, held by
+ * every GPU the library runs on until the process ends), so this call and
+ * everything under it allocate and free nothing, on the host or the device.
+ *   device        HIP device (0 .. 63) that holds the arrays
+ *   K, D, ld      as for pso_ps_create; K <= PSO_PS_STATIC_MAX_K, else
+ *                 PSO_PS_ELIMIT and nothing is enqueued
+ *   the rest      as for pso_ps_sync; same bits as pso_ps_sync
+ * All calls on one GPU share that GPU's array: calls whose work overlaps on
+ * one GPU (two streams, two threads) race on it and must be serialized by the
+ * caller; back-to-back calls on one stream are fine.  The array keeps the last
+ * call's contents; every call rewrites all of it that it reads. */
+int pso_ps_sync_static(int device, int K, int64_t D, int64_t ld, float* x, float* v,
+                       float* pbest, float* pbest_loss, const float* loss, float* gbest,
+                       float w, float c1, float c2, uint64_t seed, uint64_t step,
+                       void* hip_stream);
 
 /* Parameter averaging (Section II-B, step 5), the synchronization PSO-PS
  * replaces, on the same stacked layout: mean[d] = (x[0][d] + ... + x[K-1][d]) / K,

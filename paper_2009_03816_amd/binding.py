@@ -16,6 +16,8 @@ PSO_PS_EINVAL = -1
 PSO_PS_EALIGN = -2
 PSO_PS_EHIP = -3
 PSO_PS_ENOMEM = -4
+PSO_PS_ELIMIT = -5
+PSO_PS_STATIC_MAX_K = 4096
 
 _f32p = ctypes.c_void_p   # device addresses travel as plain pointers
 _lib = None
@@ -85,6 +87,8 @@ def load():
                                                  U64, U64, P]
     lib.pso_ps_sync_rows_history.argtypes = [P, PP, PP, PP, _f32p, _f32p, _f32p, _f32p, F, F, F,
                                              U64, U64, P]
+    lib.pso_ps_sync_static.argtypes = [I, I, I64, I64, _f32p, _f32p, _f32p, _f32p, _f32p, _f32p,
+                                       F, F, F, U64, U64, P]
     lib.pso_ps_average.argtypes = [P, _f32p, _f32p, P]
     lib.pso_ps_inertia.argtypes = [I64, I64, F, F]
     lib.pso_ps_inertia.restype = F
@@ -97,7 +101,7 @@ def load():
     for name in ("pso_ps_create", "pso_ps_sync", "pso_ps_sync_segments", "pso_ps_select",
                  "pso_ps_update", "pso_ps_last_selection", "pso_ps_set_launch",
                  "pso_ps_sync_history", "pso_ps_sync_rows", "pso_ps_average", "pso_ps_schedule",
-                 "pso_ps_sync_segments_history", "pso_ps_sync_rows_history",
+                 "pso_ps_sync_segments_history", "pso_ps_sync_rows_history", "pso_ps_sync_static",
                  "pso_ps_last_hip_error", "pso_ps_destroy"):
         getattr(lib, name).restype = I
     lib.pso_ps_strerror.restype = ctypes.c_char_p
@@ -222,6 +226,14 @@ def pso_ps_sync_rows_history(h: int, x_rows, v_rows, pbest_rows, pbest_loss, los
                                          _addr(pbest_loss), _addr(loss), _addr(gbest),
                                          _addr(gbest_loss), w, c1, c2, seed, step, _stream(stream))
     _check(rc, "pso_ps_sync_rows_history", h)
+
+
+def pso_ps_sync_static(device: int, K: int, D: int, ld: int, x, v, pbest, pbest_loss, loss, gbest,
+                       w: float, c1: float, c2: float, seed: int, step: int, stream=None) -> None:
+    rc = load().pso_ps_sync_static(device, K, D, ld, _addr(x), _addr(v), _addr(pbest),
+                                   _addr(pbest_loss), _addr(loss), _addr(gbest), w, c1, c2,
+                                   seed, step, _stream(stream))
+    _check(rc, "pso_ps_sync_static")
 
 
 def pso_ps_average(h: int, x, mean, stream=None) -> None:

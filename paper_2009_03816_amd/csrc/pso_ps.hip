@@ -49,6 +49,7 @@
 
 #include <cstdint>
 #include <cstdlib>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -592,6 +593,15 @@ struct pso_ps_ctx {
     int last_hip_error;
 };
 
+// Selection scratch of pso_ps_sync_static, which must not allocate: a
+// file-scope device array instead of a handle's hipMalloc.  Every GPU holds its
+// own copy at its own address; host code never uses the name as an address,
+// only the pointer that hipGetSymbolAddress returns for the current device.
+constexpr int kStaticMaxK = PSO_PS_STATIC_MAX_K;
+constexpr size_t kStaticScratchBytes =
+    (sizeof(Selection) + (size_t)((kStaticMaxK + 63) / 64 - 1) * sizeof(uint64_t) + 255) / 256 * 256;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
 
 // Defaults from a sweep on MI355X with K = 32, D = 25.6 M (tile = 2 KiB):
@@ -975,6 +985,36 @@ int sync_rows(pso_ps_ctx* h, float* const* x_rows, float* const* v_rows, float* 
     return PSO_PS_OK;
 }
 
+// The stage for callers that must not allocate: looks up, once per device, the
+// address that the file-scope array `scratch` has on that GPU.
+constexpr int kMaxDevices = 64;
+struct StaticDevice {
+    bool ready = false;
+    Selection* ptr = nullptr;  // device address of `scratch` on this GPU
+    bool eight_xcds = false;
+};
+StaticDevice g_static_device[kMaxDevices];
+std::mutex g_static_mutex;
+
+// Device address of the static scratch on `device` (which must be current).
+hipError_t static_scratch(int device, StaticDevice* out) {
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    StaticDevice& d = g_static_device[device];
+    if (!d.ready) {
+        void* ptr = nullptr;
+        hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        int compute_units = 0;
+        e = hipDeviceGetAttribute(&compute_units, hipDeviceAttributeMultiprocessorCount, device);
+        if (e != hipSuccess) return e;
+        d.ptr = static_cast<Selection*>(ptr);
+        d.eight_xcds = compute_units == 256;
+        d.ready = true;
+    }
+    *out = d;
+    return hipSuccess;
+}
+
 }  // namespace
 
 extern "C" {
@@ -1075,6 +1115,32 @@ int pso_ps_sync_history(pso_ps_ctx* h, float* x, float* v, float* pbest, float* 
                         float c2, uint64_t seed, uint64_t step, void* hip_stream) {
     if (!gbest_loss) return PSO_PS_EINVAL;
     return sync_flat(h, x, v, pbest, pbest_loss, loss, gbest, gbest_loss,
+                     make_params(w, c1, c2, seed, step), (hipStream_t)hip_stream);
+}
+
+int pso_ps_sync_static(int device, int K, int64_t D, int64_t ld, float* x, float* v, float* pbest,
+                       float* pbest_loss, const float* loss, float* gbest, float w, float c1,
+                       float c2, uint64_t seed, uint64_t step, void* hip_stream) {
+    if (device < 0 || device >= kMaxDevices || K < 1 || D < 1 || ld < D) return PSO_PS_EINVAL;
+    if ((uint64_t)D > (1ull << 33)) return PSO_PS_EINVAL;
+    if (K > kStaticMaxK) return PSO_PS_ELIMIT;
+    DeviceScope scope(device);
+    if (scope.err != hipSuccess) return PSO_PS_EHIP;
+    StaticDevice dev;
+    if (static_scratch(device, &dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return PSO_PS_EHIP;
+    }
+    // A handle on the stack: default launch shape, the static scratch, no
+    // segment lists (empty vectors own no memory).
+    pso_ps_ctx h;
+    h.K = K; h.D = D; h.ld = ld; h.device = device;
+    h.sel = dev.ptr; h.mask_words = (K + 63) / 64;
+    h.sel_bytes = sizeof(Selection) + (size_t)(h.mask_words - 1) * sizeof(uint64_t);
+    h.last_stream = nullptr; h.have_selection = false;
+    h.block_threads = 0; h.super_tiles = 0; h.chunk_tiles = 0; h.wgs_per_cu = 0;
+    h.force_generic = false; h.eight_xcds = dev.eight_xcds; h.last_hip_error = 0;
+    return sync_flat(&h, x, v, pbest, pbest_loss, loss, gbest, nullptr,
                      make_params(w, c1, c2, seed, step), (hipStream_t)hip_stream);
 }
 
@@ -1241,6 +1307,7 @@ const char* pso_ps_strerror(int code) {
         case PSO_PS_EALIGN: return "array not 4-byte aligned";
         case PSO_PS_EHIP: return "HIP runtime call failed";
         case PSO_PS_ENOMEM: return "host allocation failed";
+        case PSO_PS_ELIMIT: return "size beyond the fixed scratch of the allocation-free entry point";
         default: return "unknown status code";
     }
 }
