@@ -43,16 +43,68 @@ STREAM_CEILING = {
 
 
 def kernel_source_hash() -> str:
-    """Hash of the code (comments and blank lines dropped) of every file under
-    csrc/: kernels, their headers, the host launch code."""
+    """Hash of the code (comments and blank lines dropped) of the stage's
+    kernels, their header and the host launch code."""
     from paper_2009_03816_amd import build
     csrc = os.path.dirname(build.SOURCE)
     digest = hashlib.sha256()
-    for name in sorted(os.listdir(csrc)):
+    for name in ("pso_ps.hip", "tile_order.h"):
         with open(os.path.join(csrc, name), "r") as f:
             code = [line.split("//")[0].rstrip() for line in f]
         digest.update((name + "\0" + "\n".join(t for t in code if t.strip())).encode())
     return digest.hexdigest()[:16]
+
+
+def stream_probe(args) -> int:
+    """--variant stream: one arithmetic-free stream over the arrays of the
+    workload (the probes library), timed like a stage."""
+    import torch
+    from paper_2009_03816_amd import probes
+    from paper_2009_03816_amd import workloads as wl
+
+    cfg = wl.CONFIGS[args.workload]
+    K, D = cfg.K, cfg.D
+    ld = args.ld or D
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(cfg.seed)
+    x, v, p = (torch.empty(K, ld, dtype=torch.float32, device=dev).normal_(0.0, cfg.x_sigma, generator=gen)
+               for _ in range(3))
+    sink = torch.zeros(1, dtype=torch.float32, device=dev)
+    keep = x[:, :4096].clone()
+    stream = torch.cuda.current_stream()
+    shape = dict(block_threads=args.block or 128, quads=args.probe_quads,
+                 rows_per_wg=args.probe_rows_per_wg, chunked=args.probe_order == "chunked",
+                 super_tiles=args.super_tiles or 1024, chunk_tiles=args.chunk_tiles or 128,
+                 wgs_per_cu=args.wgs_per_cu or 10, nt_loads=bool(args.probe_nt_loads),
+                 nt_stores=bool(args.probe_nt_stores))
+
+    def stage(_):
+        probes.pso_ps_probe_stream(args.probe_mix, x, v, p, sink, K, D, ld,
+                                   stream=int(stream.cuda_stream), **shape)
+
+    for s in range(args.warmup):
+        stage(s)
+    elapsed, ms = time_stages(stage, 0, args.steps, stream, torch)
+    t = summary(ms)
+    if args.probe_mix != "copy":
+        assert torch.equal(x[:, :4096], keep), "the probe changed the arrays"
+    floats = {"read": 3, "copy": 2, "inplace": 5}[args.probe_mix]
+    nbytes = 4.0 * K * D * floats
+    gbs = nbytes / (t["avg"] * 1e-3) / 1e9
+    print(json.dumps({
+        "metric": "stream probe GB/s", "value": gbs, "unit": "GB/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: K={K} x D={D} fp32, row stride {ld}",
+                   "variant": "stream", "mix": args.probe_mix, **shape},
+        "roofline": {"bound": "hbm", "kernel": "stream_kernel", "achieved": gbs,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
+                     "traffic": None, "algorithmic_bytes_per_launch": nbytes,
+                     "kernel_ms_avg": t["avg"], "kernel_ms_median": t["median"],
+                     "kernel_ms_min": t["min"]}}))
+    return 0
 
 
 def cpu_baseline(cfg, seconds_target: float = 15.0, all_cores: bool = True):
@@ -125,18 +177,23 @@ def cpu_baseline(cfg, seconds_target: float = 15.0, all_cores: bool = True):
     return out
 
 
-def time_stages(stage, first, count, stream, torch):
-    """Enqueue `count` stages with an event before the first and after each, wait
-    once, and return (wall seconds, per-stage milliseconds)."""
+def time_stages(stage, first, count, stream, torch, per_stage_events=True):
+    """Enqueue `count` stages, wait once, and return (wall seconds, per-stage
+    milliseconds).  With per_stage_events an event is recorded after every
+    stage; without, only before the first and after the last (nothing but the
+    stages' own kernels sits in the stream) and every stage is given the mean."""
     marks = [torch.cuda.Event(enable_timing=True) for _ in range(count + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     marks[0].record(stream)
     for k in range(count):
         stage(first + k)
-        marks[k + 1].record(stream)
+        if per_stage_events or k == count - 1:
+            marks[k + 1].record(stream)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    if not per_stage_events:
+        return elapsed, [marks[0].elapsed_time(marks[count]) / count] * count
     return elapsed, [marks[k].elapsed_time(marks[k + 1]) for k in range(count)]
 
 
@@ -156,15 +213,28 @@ def main() -> int:
     ap.add_argument("--wgs-per-cu", type=int, default=0)
     ap.add_argument("--force-generic", action="store_true",
                     help="element-wise path instead of the 128-bit one (a measurement of that path)")
+    ap.add_argument("--fused-rows", type=int, default=0,
+                    help="sync, history: the single-pass kernels with this many rows in flight per "
+                         "workgroup (pso_ps_set_variant) instead of the default two kernels")
+    ap.add_argument("--ld", type=int, default=0,
+                    help="row stride in elements (default D, the dense layout of the metric)")
     ap.add_argument("--misalign", default="",
                     help="four element offsets 'x,v,pbest,gbest' of the arrays inside their "
                          "allocations (default: all 0, i.e. 16-byte aligned and congruent)")
     ap.add_argument("--variant", default="sync",
-                    choices=["sync", "history", "rows", "segments", "average"],
+                    choices=["sync", "history", "rows", "segments", "average", "stream"],
                     help="sync: the stage (default, the headline); history: historical gBest; "
                          "rows: K separate per-worker arrays; segments: one [K, n] array per "
                          "parameter tensor (needs a workload with a segment list); "
-                         "average: parameter averaging")
+                         "average: parameter averaging; stream: an arithmetic-free stream over "
+                         "the same arrays (the --probe-* options), a measured ceiling")
+    ap.add_argument("--probe-mix", default="inplace", choices=["read", "copy", "inplace"],
+                    help="stream: read x, v, pbest / copy x to v / read all three and write x, v back")
+    ap.add_argument("--probe-order", default="chunked", choices=["plain", "chunked"])
+    ap.add_argument("--probe-rows-per-wg", type=int, default=1)
+    ap.add_argument("--probe-quads", type=int, default=1)
+    ap.add_argument("--probe-nt-loads", type=int, default=1)
+    ap.add_argument("--probe-nt-stores", type=int, default=1)
     ap.add_argument("--graph", action="store_true",
                     help="sync only: also replay the stages from a HIP graph and report that time")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -184,6 +254,8 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 3
+    if args.variant == "stream":
+        return stream_probe(args)
     cfg = wl.CONFIGS[args.workload]
     K, D = cfg.K, cfg.D
     dev = torch.device("cuda:0")
@@ -197,7 +269,8 @@ def main() -> int:
         view.copy_(torch.from_numpy(a))
         return view
 
-    sw = wl.make_swarm(cfg, steps=total)
+    ld = args.ld or D
+    sw = wl.make_swarm(cfg, ld=ld, steps=total)
     if args.variant == "rows":                           # K separately allocated arrays
         xr = [shifted(sw.x[i], offs[0]) for i in range(K)]
         vr = [shifted(sw.v[i], offs[1]) for i in range(K)]
@@ -222,10 +295,12 @@ def main() -> int:
     del sw
 
     h = pso.pso_ps_create(K, D, D, seg_sizes=list(cfg.segments)) if args.variant == "segments" \
-        else pso.pso_ps_create(K, D)
+        else pso.pso_ps_create(K, D, ld)
     if args.block or args.super_tiles or args.chunk_tiles or args.wgs_per_cu or args.force_generic:
         pso.pso_ps_set_launch(h, args.block, args.super_tiles, args.chunk_tiles, args.wgs_per_cu,
                               args.force_generic)
+    if args.fused_rows:
+        pso.pso_ps_set_variant(h, args.fused_rows)
     stream = torch.cuda.current_stream()
 
     def stage(s):
@@ -247,14 +322,16 @@ def main() -> int:
     # -- the timed region: K whole stages through the entry point ---------------------------
     for s in range(args.warmup):
         stage(s)
-    elapsed, stage_ms = time_stages(stage, args.warmup, args.steps, stream, torch)
+    elapsed, stage_ms = time_stages(stage, args.warmup, args.steps, stream, torch,
+                                    per_stage_events=False)
     stage_t = summary(stage_ms)
 
     # -- a second pass over as many stages, split at the kernel boundary --------------------
     # (sync only: pso_ps_select + pso_ps_update are the two halves of pso_ps_sync, bit for
     # bit; an event between them gives each kernel's own duration on the launch stream)
     select_ms, update_ms = [], []
-    if args.variant == "sync":
+    split_pass = args.variant == "sync" and not args.fused_rows
+    if split_pass:
         marks = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
         for k in range(args.steps):
             s = args.warmup + args.steps + k
@@ -302,9 +379,9 @@ def main() -> int:
                   "history": "select_gbest_kernel + update_kernel"}[args.variant]
     stage_gbs = stage_bytes / (stage_t["avg"] * 1e-3) / 1e9
     stage_roof = {
-        "what": "the whole entry-point call, events around each of the timed stages",
-        "bytes": stage_bytes, "ms_avg": stage_t["avg"], "ms_median": stage_t["median"],
-        "ms_min": stage_t["min"], "achieved": stage_gbs, "frac": stage_gbs / HBM_PEAK_GBS,
+        "what": "the whole entry-point call: one event before the first and one after the last "
+                "of the timed stages, divided by their number",
+        "bytes": stage_bytes, "ms_avg": stage_t["avg"], "achieved": stage_gbs, "frac": stage_gbs / HBM_PEAK_GBS,
         "bytes_are": "algorithmic minimum 4*D*(5K+1): x, v read and written, pbest read or "
                      "written, gbest written once; the two-kernel split moves 4*D*(5K+3)"
         if args.variant != "average" else "4*D*(2K+1)"}
@@ -334,12 +411,14 @@ def main() -> int:
         dst.copy_(src)
         torch.cuda.synchronize()
 
-    if args.variant == "sync":
+    if args.fused_rows and args.variant in ("sync", "history"):
+        kernel = "select_only_kernel + fused_rows_kernel"
+    if split_pass:
         upd, sel = summary(update_ms), summary(select_ms)
         kernel_bytes = 4.0 * D * (5 * K + 1)             # per update launch: 20 B per particle
         achieved = kernel_bytes / (upd["avg"] * 1e-3) / 1e9   # parameter + first read of gbest
         default_shape = not (args.block or args.super_tiles or args.chunk_tiles or args.wgs_per_cu
-                             or args.force_generic or args.misalign)
+                             or args.force_generic or args.misalign or args.ld)
         key = (cfg.name, kernel_source_hash())
         traffic = MEASURED_TRAFFIC.get(key) if default_shape else None
         roofline = {
@@ -385,9 +464,11 @@ def main() -> int:
                                    "average": "pso_ps_average"}[args.variant]},
         "roofline": roofline,
     }
-    if args.force_generic or args.misalign:
+    if args.force_generic or args.misalign or args.fused_rows or args.ld:
         out["config"]["path"] = ("element-wise (forced)" if args.force_generic else "128-bit") + \
-            (f", array offsets {offs}" if args.misalign else "")
+            (f", array offsets {offs}" if args.misalign else "") + \
+            (f", single pass with {args.fused_rows} rows in flight" if args.fused_rows else "") + \
+            (f", row stride {ld}" if args.ld else "")
     torch.cuda.synchronize()
     pso.pso_ps_destroy(h)
     del dx, dg

@@ -226,6 +226,20 @@ int pso_ps_last_selection(pso_ps_ctx* h, int* g_out, uint64_t* improved_mask_out
 int pso_ps_set_launch(pso_ps_ctx* h, int block_threads, int super_tiles, int chunk_tiles,
                       int wgs_per_cu, int force_generic);
 
+/* Which kernels pso_ps_sync and pso_ps_sync_history use on this handle;
+ * results are bitwise the same either way.
+ *   fused_rows = 0  (default) selection + gbest copy, then the update pass with
+ *                   one workgroup per (particle, tile), gbest re-read through
+ *                   the caches;
+ *   fused_rows = P  in {1, 2, 3, 4, 6, 8}: a one-wavefront selection launch, then
+ *                   a single pass in which one workgroup owns a tile of columns
+ *                   for all K particles, keeps its piece of gbest on chip and
+ *                   has the loads of P particles in flight (block_threads 64,
+ *                   128 or 256).  Moves the fewest bytes; kept for measurement,
+ *                   see the kernel's comment for when it is slower.
+ * The other entry points ignore it. */
+int pso_ps_set_variant(pso_ps_ctx* h, int fused_rows);
+
 /* hipError_t (as int) of the last failed HIP call on this handle, 0 if none. */
 int pso_ps_last_hip_error(const pso_ps_ctx* h);
 

@@ -1,0 +1,45 @@
+/* pso_ps_probes.h - C ABI of the stream probes: arithmetic-free kernels that
+ * measure what one AMD GPU's memory system gives to the access mix of the
+ * PSO-PS update pass (Eq. (6), (7) of the paper read x, v and pbest of every
+ * particle and write x and v back) and to simpler mixes, under the launch
+ * shapes the update kernel can choose from.  Measurement only: the benchmark
+ * prints these rates as ceilings next to the kernels' own; the library of the
+ * synchronization stage never calls this one.
+ */
+#ifndef PSO_PS_PROBES_H
+#define PSO_PS_PROBES_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Enqueue one stream over the K rows of D floats (row stride ld) of the device
+ * arrays x, v, pbest on hip_stream and return without waiting.
+ *   mix          0: read x, v, pbest (3 K D floats read)
+ *                1: copy x -> v (K D read, K D written; v is overwritten)
+ *                2: read x, v, pbest and write x, v back unchanged (the update
+ *                   pass's mix, 3 reads + 2 writes; the arrays keep their values)
+ *   sink         device, 1 float; never written in practice (keeps loads alive)
+ *   block_threads 64, 128 or 256; quads 1 or 2: 128-bit accesses per thread and
+ *                array; a tile is block_threads * 4 * quads floats of one row
+ *   rows_per_wg  R >= 1: one workgroup walks R consecutive rows of its tile
+ *   chunked      0: workgroup b takes tile b % tiles of row b / tiles;
+ *                1: the XCD-aware order of the update pass with super_tiles and
+ *                   chunk_tiles (powers of two; used only if chunked)
+ *   wgs_per_cu   cap on resident workgroups per compute unit (3..63), by an LDS
+ *                reservation that is never touched; other values: no cap
+ *   nt_loads, nt_stores  != 0: non-temporal accesses
+ * The arrays must be 16-byte aligned and ld a multiple of 4 (K > 1); the first
+ * and last partial 16 bytes of a row are skipped.
+ * Returns 0, -1 (bad argument), -2 (alignment) or -3 (launch failed). */
+int pso_ps_probe_stream(int mix, float* x, float* v, float* pbest, float* sink, int K,
+                        int64_t D, int64_t ld, int block_threads, int quads, int rows_per_wg,
+                        int chunked, int super_tiles, int chunk_tiles, int wgs_per_cu,
+                        int nt_loads, int nt_stores, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PSO_PS_PROBES_H */

@@ -95,11 +95,12 @@ def load():
     lib.pso_ps_schedule.argtypes = [I64, I64, I64, I64, F, F, F, F, ctypes.POINTER(I),
                                     ctypes.POINTER(F), ctypes.POINTER(F), ctypes.POINTER(F)]
     lib.pso_ps_set_launch.argtypes = [P, I, I, I, I, I]
+    lib.pso_ps_set_variant.argtypes = [P, I]
     lib.pso_ps_last_hip_error.argtypes = [P]
     lib.pso_ps_destroy.argtypes = [P]
     lib.pso_ps_strerror.argtypes = [I]
     for name in ("pso_ps_create", "pso_ps_sync", "pso_ps_sync_segments", "pso_ps_select",
-                 "pso_ps_update", "pso_ps_last_selection", "pso_ps_set_launch",
+                 "pso_ps_update", "pso_ps_last_selection", "pso_ps_set_launch", "pso_ps_set_variant",
                  "pso_ps_sync_history", "pso_ps_sync_rows", "pso_ps_average", "pso_ps_schedule",
                  "pso_ps_sync_segments_history", "pso_ps_sync_rows_history", "pso_ps_sync_static",
                  "pso_ps_last_hip_error", "pso_ps_destroy"):
@@ -260,6 +261,10 @@ def pso_ps_set_launch(h: int, block_threads: int = 0, super_tiles: int = 0, chun
                       wgs_per_cu: int = 0, force_generic: bool = False) -> None:
     _check(load().pso_ps_set_launch(h, block_threads, super_tiles, chunk_tiles, wgs_per_cu,
                                     int(force_generic)), "pso_ps_set_launch", h)
+
+
+def pso_ps_set_variant(h: int, fused_rows: int = 0) -> None:
+    _check(load().pso_ps_set_variant(h, fused_rows), "pso_ps_set_variant", h)
 
 
 def pso_ps_source_hash() -> str:

@@ -1,4 +1,5 @@
-"""Compiles csrc/pso_ps.hip into libpso_ps.so (in-tree) with hipcc for gfx950."""
+"""Compiles csrc/pso_ps.hip into libpso_ps.so and csrc/stream_probes.hip into
+libpso_ps_probes.so (both in-tree) with hipcc for gfx950."""
 from __future__ import annotations
 
 import hashlib
@@ -11,6 +12,8 @@ _ROOT = os.path.dirname(_PKG)
 SOURCE = os.path.join(_PKG, "csrc", "pso_ps.hip")
 INCLUDE = os.path.join(_ROOT, "include")
 LIBRARY = os.path.join(_PKG, "libpso_ps.so")
+PROBES_SOURCE = os.path.join(_PKG, "csrc", "stream_probes.hip")
+PROBES_LIBRARY = os.path.join(_PKG, "libpso_ps_probes.so")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -30,10 +33,9 @@ def hipcc() -> str:
 
 
 def source_files() -> list:
-    """Everything the library is compiled from."""
+    """Everything the stage's library is compiled from."""
     csrc = os.path.dirname(SOURCE)
-    return sorted(os.path.join(csrc, n) for n in os.listdir(csrc)) + \
-        [os.path.join(INCLUDE, "pso_ps.h")]
+    return [SOURCE, os.path.join(csrc, "tile_order.h"), os.path.join(INCLUDE, "pso_ps.h")]
 
 
 def source_hash() -> str:
@@ -59,5 +61,17 @@ def build_library(verbose: bool = False) -> str:
     return LIBRARY
 
 
+def build_probes(verbose: bool = False) -> str:
+    """Always compiles the stream probes (measurement only); returns the path."""
+    tmp = PROBES_LIBRARY + ".tmp.%d" % os.getpid()
+    cmd = [hipcc(), *HIPCC_FLAGS, "-I", INCLUDE, "-o", tmp, PROBES_SOURCE]
+    if verbose:
+        print(" ".join(cmd))
+    subprocess.run(cmd, check=True)
+    os.replace(tmp, PROBES_LIBRARY)
+    return PROBES_LIBRARY
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))
+    print(build_probes(verbose=True))

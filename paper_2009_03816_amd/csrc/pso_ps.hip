@@ -506,6 +506,141 @@ __global__ __launch_bounds__(kCopyBlock) void select_gbest_segments_kernel(
     copy_tile(e.x + (long long)g * e.n, e.gbest, e.n, tile);
 }
 
+// ---------------------------------------------------------------------------
+// The single-pass variant: one workgroup owns a tile of columns for ALL K
+// rows.  It reads its piece of x_g once, keeps it on chip (every thread needs
+// only its own four columns of it, so registers serve; staging through LDS
+// would add a round trip and share nothing), writes it to gbest, and walks the
+// rows with the loads of the next P rows in flight while one row is computed.
+// This moves the algorithmic minimum, 4 D (5K + 1) bytes, in one launch after
+// a one-wavefront selection launch, and no workgroup reads what another
+// writes.  Tiles are common to all rows, so only rows whose address is
+// congruent to row 0's modulo 128 bytes get line-aligned accesses.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void select_only_kernel(int K, const float* __restrict__ loss,
+                                                         float* pbest_loss, Selection* sel,
+                                                         const float* gbest_loss) {
+    int g;
+    bool replace;
+    select_or_recall(K, loss, pbest_loss, sel, gbest_loss, 1, &g, &replace);
+}
+
+// Columns c .. c+3 of a row of n columns: one 128-bit access where all four
+// exist (whole), else element by element.
+__device__ __forceinline__ f32x4 load_quad(const float* __restrict__ row, long long c, long long n,
+                                           bool whole) {
+    if (whole) return __builtin_nontemporal_load(reinterpret_cast<const f32x4_a4*>(row + c));
+    f32x4 r = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (c >= 0 && c < n) r.x = row[c];
+    if (c + 1 >= 0 && c + 1 < n) r.y = row[c + 1];
+    if (c + 2 >= 0 && c + 2 < n) r.z = row[c + 2];
+    if (c + 3 >= 0 && c + 3 < n) r.w = row[c + 3];
+    return r;
+}
+
+__device__ __forceinline__ void store_quad(float* __restrict__ row, long long c, long long n,
+                                           bool whole, f32x4 q) {
+    if (whole) {
+        __builtin_nontemporal_store(q, reinterpret_cast<f32x4_a4*>(row + c));
+        return;
+    }
+    if (c >= 0 && c < n) row[c] = q.x;
+    if (c + 1 >= 0 && c + 1 < n) row[c + 1] = q.y;
+    if (c + 2 >= 0 && c + 2 < n) row[c + 2] = q.z;
+    if (c + 3 >= 0 && c + 3 < n) row[c + 3] = q.w;
+}
+
+template <int BLOCK, int P, bool ODD>
+__device__ __forceinline__ void fused_tile(const ColumnBlock& b, int K,
+                                           const Selection* __restrict__ sel, const MoveParams& m,
+                                           long long c) {
+    const bool whole = c >= 0 && c + 4 <= b.n;
+    const int g = sel->g;
+    const bool replaced = sel->replaced != 0;
+
+    // gbest for these columns: x_g as it is before anybody moves (Algorithm 3),
+    // or the kept historical gbest.
+    f32x4 gb;
+    if (replaced) {
+        gb = load_quad(b.x + (long long)g * b.ld, c, b.n, whole);
+        store_quad(b.gbest, c, b.n, whole, gb);
+    } else {
+        gb = load_quad(b.gbest, c, b.n, whole);
+    }
+
+    // Flat index of column c; may be negative in the first tile, whose columns
+    // below 0 do not exist (arithmetic shift keeps the pairs of the others right).
+    const long long d = (long long)b.d0 + c;
+    const uint32_t pair = (uint32_t)(d >> 1);
+
+    f32x4 xq[P], vq[P], pq[P];
+    unsigned long long mask = 0;
+    auto improved_bit = [&](int i) { return (sel->improved[i >> 6] >> (i & 63)) & 1ull; };
+    auto fetch = [&](int i, f32x4& xo, f32x4& vo, f32x4& po) {
+        const long long row = (long long)i * b.ld;
+        xo = (replaced && i == g) ? gb : load_quad(b.x + row, c, b.n, whole);
+        vo = load_quad(b.v + row, c, b.n, whole);
+        po = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        if (!improved_bit(i)) po = load_quad(b.pbest + row, c, b.n, whole);
+    };
+#pragma unroll
+    for (int s = 0; s < P; ++s)
+        if (s < K) fetch(s, xq[s], vq[s], pq[s]);
+    (void)mask;
+
+    for (int base = 0; base < K; base += P) {
+#pragma unroll
+        for (int s = 0; s < P; ++s) {
+            const int i = base + s;
+            if (i >= K) break;
+            const bool improved = improved_bit(i);
+            const Words4 ra = philox4x32_10(pair, (uint32_t)i, m.step_lo, m.step_hi, m.key0, m.key1);
+            const Words4 rb = philox4x32_10(pair + 1u, (uint32_t)i, m.step_lo, m.step_hi, m.key0, m.key1);
+            Words4 rc = rb;
+            if (ODD) rc = philox4x32_10(pair + 2u, (uint32_t)i, m.step_lo, m.step_hi, m.key0, m.key1);
+            const f32x4 x_old = xq[s];
+            const f32x4 pv = improved ? x_old : pq[s];
+            float xs[4] = {x_old.x, x_old.y, x_old.z, x_old.w};
+            float vs[4] = {vq[s].x, vq[s].y, vq[s].z, vq[s].w};
+            if (!ODD) {
+                move_element(xs[0], vs[0], pv.x, gb.x, ra.s0, ra.s1, m);
+                move_element(xs[1], vs[1], pv.y, gb.y, ra.s2, ra.s3, m);
+                move_element(xs[2], vs[2], pv.z, gb.z, rb.s0, rb.s1, m);
+                move_element(xs[3], vs[3], pv.w, gb.w, rb.s2, rb.s3, m);
+            } else {
+                move_element(xs[0], vs[0], pv.x, gb.x, ra.s2, ra.s3, m);
+                move_element(xs[1], vs[1], pv.y, gb.y, rb.s0, rb.s1, m);
+                move_element(xs[2], vs[2], pv.z, gb.z, rb.s2, rb.s3, m);
+                move_element(xs[3], vs[3], pv.w, gb.w, rc.s0, rc.s1, m);
+            }
+            const long long row = (long long)i * b.ld;
+            store_quad(b.x + row, c, b.n, whole, f32x4{xs[0], xs[1], xs[2], xs[3]});
+            store_quad(b.v + row, c, b.n, whole, f32x4{vs[0], vs[1], vs[2], vs[3]});
+            if (improved) store_quad(b.pbest + row, c, b.n, whole, x_old);
+            if (i + P < K) fetch(i + P, xq[s], vq[s], pq[s]);
+        }
+    }
+}
+
+template <int BLOCK, int P>
+__global__ __launch_bounds__(BLOCK) void fused_rows_kernel(ColumnBlock b, int K,
+                                                           const Selection* __restrict__ sel,
+                                                           MoveParams m, TileOrder ord,
+                                                           float* gbest_loss) {
+    if (gbest_loss && blockIdx.x == 0 && threadIdx.x == 0) *gbest_loss = sel->gbest_loss;
+    unsigned row, tile;
+    if (!decode_tile_order(ord, 1u, blockIdx.x, &row, &tile)) return;
+    constexpr unsigned TILE = BLOCK * 4;
+    // tiles are aligned to the address of row 0
+    const long long phase = (long long)((reinterpret_cast<uintptr_t>(b.x) >> 2) & (TILE - 1u));
+    const long long c = (long long)tile * TILE - phase + 4 * (long long)threadIdx.x;
+    if (c + 4 <= 0 || c >= b.n) return;
+    if (((unsigned long long)phase + b.d0) & 1ull)
+        fused_tile<BLOCK, P, true>(b, K, sel, m, c);
+    else
+        fused_tile<BLOCK, P, false>(b, K, sel, m, c);
+}
+
 // Parameter averaging (Section II-B, step 5) on the stacked layout, first half:
 // one thread owns four columns, sums the K rows in order and divides by K.
 // Reading K rows at one column is tolerant of the rows' different alignments.
@@ -521,6 +656,8 @@ __global__ __launch_bounds__(BLOCK) void mean_kernel(const float* __restrict__ x
     if (c >= n) return;
     const float kf = (float)K;
     if (c + 4 <= n) {
+        // (issuing several rows' loads before the first add changes nothing: the
+        // pass is bound by the K rows it has open at once, not by latency)
         f32x4 sum = __builtin_nontemporal_load(reinterpret_cast<const f32x4_a4*>(x + c));
         for (int k = 1; k < K; ++k)
             sum = sum + __builtin_nontemporal_load(
@@ -589,6 +726,7 @@ struct pso_ps_ctx {
     int chunk_tiles;       // 0 = default; else a power of two <= super_tiles
     int wgs_per_cu;        // 0 = default; else cap on resident update workgroups per compute unit
     bool force_generic;
+    int fused_rows;        // 0: selection/copy kernel + update kernel; P > 0: single pass, P rows in flight
     bool eight_xcds;       // 256 compute units: the chip is driven as one device of 8 XCDs
     int last_hip_error;
 };
@@ -604,8 +742,10 @@ static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace {
 
-// Defaults from a sweep on MI355X with K = 32, D = 25.6 M (tile = 2 KiB):
-constexpr int kDefaultBlock = 128;
+// Defaults from sweeps on MI355X with K = 32, D = 25.6 M: one wavefront per
+// workgroup (tile = 1 KiB; 64 threads beat 128 by just under 1 %, 256 lose 3 %),
+constexpr int kDefaultBlock = 64;
+constexpr int kRowsBlock = 128;                      // update_rows_kernel
 constexpr unsigned kDefaultSuperBytes = 2u << 20;    // gbest footprint per XCD, in its 4 MiB L2
 constexpr unsigned kDefaultChunkBytes = 256u << 10;  // consecutive addresses handed to one XCD
 constexpr int kDefaultWavesPerCu = 20;               // resident wavefronts per compute unit (of 32)
@@ -700,6 +840,9 @@ unsigned long long tiles_per_row(int rows, long long n, bool aligned_to_rows, un
 }
 
 int block_of(const pso_ps_ctx* h) { return h->block_threads ? h->block_threads : kDefaultBlock; }
+// Row-pointer launches fetch their row's three pointers from the kernel
+// arguments first; twice the workgroups pay that twice (2.64 against 2.51 ms).
+int rows_block_of(const pso_ps_ctx* h) { return h->block_threads ? h->block_threads : kRowsBlock; }
 
 #define PSO_PS_DISPATCH_BLOCK(h, e, CALL)   \
     switch (block_of(h)) {                  \
@@ -803,9 +946,57 @@ int enqueue_update(pso_ps_ctx* h, const ColumnBlock& b, const MoveParams& m, flo
 int enqueue_update_rows(pso_ps_ctx* h, const RowTable& tab, const float* gbest, int row0, int rows,
                         const MoveParams& m, float* gbest_loss, hipStream_t stream) {
     hipError_t e;
-#define CALL(B) launch_update_rows<B>(h, tab, gbest, row0, rows, m, gbest_loss, stream)
-    PSO_PS_DISPATCH_BLOCK(h, e, CALL)
-#undef CALL
+    switch (rows_block_of(h)) {
+        case 64: e = launch_update_rows<64>(h, tab, gbest, row0, rows, m, gbest_loss, stream); break;
+        case 128: e = launch_update_rows<128>(h, tab, gbest, row0, rows, m, gbest_loss, stream); break;
+        case 256: e = launch_update_rows<256>(h, tab, gbest, row0, rows, m, gbest_loss, stream); break;
+        case 512: e = launch_update_rows<512>(h, tab, gbest, row0, rows, m, gbest_loss, stream); break;
+        case 1024: e = launch_update_rows<1024>(h, tab, gbest, row0, rows, m, gbest_loss, stream); break;
+        default: return PSO_PS_EINVAL;
+    }
+    return e == hipSuccess ? PSO_PS_OK : hip_fail(h, e);
+}
+
+// The single-pass variant of the flat stage: a one-wavefront selection launch,
+// then one launch that walks all K rows of each column tile.
+template <int BLOCK>
+hipError_t launch_fused(const pso_ps_ctx* h, const ColumnBlock& b, const MoveParams& m,
+                        float* gbest_loss, hipStream_t stream) {
+    TileOrder ord;
+    unsigned long long grid = 0;
+    const unsigned long long tiles = tiles_per_row(1, b.n, true, BLOCK * 4u, [&](int) { return b.x; });
+    if (!plan_order(h, 1, tiles, BLOCK * 4u, &ord, &grid)) return hipErrorInvalidConfiguration;
+    const unsigned lds = occupancy_cap_lds(h, BLOCK);
+#define PSO_PS_FUSED(P)                                                                          \
+    hipLaunchKernelGGL((fused_rows_kernel<BLOCK, P>), dim3((unsigned)grid), dim3(BLOCK), lds,    \
+                       stream, b, h->K, (const Selection*)h->sel, m, ord, gbest_loss)
+    switch (h->fused_rows) {
+        case 1: PSO_PS_FUSED(1); break;
+        case 2: PSO_PS_FUSED(2); break;
+        case 3: PSO_PS_FUSED(3); break;
+        case 4: PSO_PS_FUSED(4); break;
+        case 6: PSO_PS_FUSED(6); break;
+        case 8: PSO_PS_FUSED(8); break;
+        default: return hipErrorInvalidValue;
+    }
+#undef PSO_PS_FUSED
+    return hipGetLastError();
+}
+
+int enqueue_fused(pso_ps_ctx* h, const ColumnBlock& b, float* pbest_loss, const float* loss,
+                  const MoveParams& m, float* gbest_loss, hipStream_t stream) {
+    hipLaunchKernelGGL(select_only_kernel, dim3(1), dim3(64), 0, stream, h->K, loss, pbest_loss,
+                       h->sel, (const float*)gbest_loss);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(h, e);
+    h->last_stream = stream;
+    h->have_selection = true;
+    switch (block_of(h)) {
+        case 64: e = launch_fused<64>(h, b, m, gbest_loss, stream); break;
+        case 128: e = launch_fused<128>(h, b, m, gbest_loss, stream); break;
+        case 256: e = launch_fused<256>(h, b, m, gbest_loss, stream); break;
+        default: return PSO_PS_EINVAL;
+    }
     return e == hipSuccess ? PSO_PS_OK : hip_fail(h, e);
 }
 
@@ -830,6 +1021,7 @@ int sync_flat(pso_ps_ctx* h, float* x, float* v, float* pbest, float* pbest_loss
     if (rc != PSO_PS_OK) return rc;
     DeviceScope scope(h->device);
     if (scope.err != hipSuccess) return hip_fail(h, scope.err);
+    if (h->fused_rows > 0) return enqueue_fused(h, b, pbest_loss, loss, m, gbest_loss, stream);
     rc = enqueue_select_gbest(h, pbest_loss, loss, StackedSource{x, b.ld}, h->K,
                               [&](int i) { return x + (long long)i * b.ld; }, gbest, b.n,
                               gbest_loss, true, stream);
@@ -1055,7 +1247,7 @@ int pso_ps_create(pso_ps_ctx** out, int K, int64_t D, int64_t ld, int n_seg,
     h->sel_bytes = sizeof(Selection) + (size_t)(h->mask_words - 1) * sizeof(uint64_t);
     h->sel = nullptr; h->last_stream = nullptr; h->have_selection = false;
     h->block_threads = 0; h->super_tiles = 0; h->chunk_tiles = 0; h->wgs_per_cu = 0;
-    h->force_generic = false; h->eight_xcds = true; h->last_hip_error = 0;
+    h->force_generic = false; h->fused_rows = 0; h->eight_xcds = true; h->last_hip_error = 0;
 
     DeviceScope scope(device);
     hipError_t e = scope.err;
@@ -1139,7 +1331,7 @@ int pso_ps_sync_static(int device, int K, int64_t D, int64_t ld, float* x, float
     h.sel_bytes = sizeof(Selection) + (size_t)(h.mask_words - 1) * sizeof(uint64_t);
     h.last_stream = nullptr; h.have_selection = false;
     h.block_threads = 0; h.super_tiles = 0; h.chunk_tiles = 0; h.wgs_per_cu = 0;
-    h.force_generic = false; h.eight_xcds = dev.eight_xcds; h.last_hip_error = 0;
+    h.force_generic = false; h.fused_rows = 0; h.eight_xcds = dev.eight_xcds; h.last_hip_error = 0;
     return sync_flat(&h, x, v, pbest, pbest_loss, loss, gbest, nullptr,
                      make_params(w, c1, c2, seed, step), (hipStream_t)hip_stream);
 }
@@ -1197,7 +1389,7 @@ int pso_ps_average(pso_ps_ctx* h, float* x, float* mean, void* hip_stream) {
     // Tiles are aligned to each row's own address, so any 4-byte aligned row
     // can take the 128-bit stores.
     const bool vec = !h->force_generic;
-    constexpr int BLOCK = kDefaultBlock;
+    constexpr int BLOCK = 128;  // a write-only stream wants 128 threads: 64 cost 17 % here
     TileOrder ord;
     unsigned long long grid = 0;
     const unsigned long long tiles =
@@ -1275,6 +1467,16 @@ int pso_ps_set_launch(pso_ps_ctx* h, int block_threads, int super_tiles, int chu
     h->chunk_tiles = chunk_tiles;
     h->wgs_per_cu = wgs_per_cu;
     h->force_generic = force_generic != 0;
+    return PSO_PS_OK;
+}
+
+int pso_ps_set_variant(pso_ps_ctx* h, int fused_rows) {
+    if (!h) return PSO_PS_EINVAL;
+    switch (fused_rows) {
+        case 0: case 1: case 2: case 3: case 4: case 6: case 8: break;
+        default: return PSO_PS_EINVAL;
+    }
+    h->fused_rows = fused_rows;
     return PSO_PS_OK;
 }
 

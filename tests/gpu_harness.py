@@ -54,7 +54,8 @@ class Pair:
     the oracle."""
 
     def __init__(self, sw, offset=0, block_threads: int = 0, super_tiles: int = 0,
-                 chunk_tiles: int = 0, wgs_per_cu: int = 0, force_generic: bool = False):
+                 chunk_tiles: int = 0, wgs_per_cu: int = 0, force_generic: bool = False,
+                 fused_rows: int = 0):
         """offset: elements by which every device array is shifted inside its
         allocation, or four of them for x, v, pbest and gbest."""
         self.sw, self.K, self.D, self.ld = sw, sw.cfg.K, sw.cfg.D, sw.ld
@@ -69,6 +70,8 @@ class Pair:
         if block_threads or super_tiles or chunk_tiles or wgs_per_cu or force_generic:
             pso.pso_ps_set_launch(self.h, block_threads, super_tiles, chunk_tiles, wgs_per_cu,
                                   force_generic)
+        if fused_rows:
+            pso.pso_ps_set_variant(self.h, fused_rows)
 
     def close(self):
         torch.cuda.synchronize()

@@ -44,3 +44,19 @@ def test_status_texts_and_argument_checks_without_a_gpu():
         == pso.PSO_PS_EINVAL
     assert lib.pso_ps_destroy(None) == pso.PSO_PS_OK
     assert h.value is None
+
+
+def test_probe_library_exports_what_its_header_declares():
+    from paper_2009_03816_amd import build
+    text = open(os.path.join(ROOT, "include", "pso_ps_probes.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = sorted(set(re.findall(r"\b(pso_ps_[a-z_]+)\s*\(", text)))
+    assert names == ["pso_ps_probe_stream"]
+    if not os.path.exists(build.PROBES_LIBRARY):
+        build.build_probes()
+    lib = ctypes.CDLL(build.PROBES_LIBRARY)
+    for name in names:
+        assert hasattr(lib, name), name
+    # rejected before any HIP call is made
+    assert lib.pso_ps_probe_stream(2, None, None, None, None, 4, 16, 16, 128, 1, 1, 1, 1024, 128,
+                                   10, 1, 1, None) == -1

@@ -56,6 +56,56 @@ def test_history_trajectory(oracle, K, D, steps):
         pso.pso_ps_destroy(h)
 
 
+@pytest.mark.parametrize("fused_rows,block", [(1, 0), (2, 64), (3, 128), (4, 256), (6, 0), (8, 64)])
+@pytest.mark.parametrize("K,D,ld,offset", [
+    (1, 3, 3, 0), (2, 7, 7, 0), (5, 4_098, 4_098, 0), (7, 4_099, 4_099, 0),      # K below / not a multiple of P
+    (9, 70_002, 70_004, (1, 2, 3, 0)),         # odd start: three Philox calls per four columns
+    (33, 1_500, 1_501, (2, 0, 1, 3)),          # odd stride
+    (70, 300, 300, 0),                         # two words of improved flags
+])
+def test_single_pass_variant(oracle, fused_rows, block, K, D, ld, offset):
+    """The single-pass kernels (one workgroup walks all K rows of its columns,
+    gbest kept on chip) give the bits of the oracle as well, with history too."""
+    print(f"[case] single pass P={fused_rows} block={block} K={K} D={D} ld={ld} offset={offset}",
+          flush=True)
+    sw = wl.small_swarm(K, D, seed=300 + K + fused_rows, ld=ld, steps=3)
+    sw.x[:, D:] = 7.0; sw.v[:, D:] = 7.0; sw.pbest[:, D:] = 7.0
+    pair = gh.Pair(sw, offset=offset, block_threads=block, fused_rows=fused_rows)
+    try:
+        for s in range(3):
+            g, improved = pair.step(oracle, s)
+            pair.check(g, improved, f"single pass step {s}")
+    finally:
+        pair.close()
+    # historical gBest through the same kernels, with a stage that keeps the old gbest
+    losses = sw.losses.copy()
+    losses[1] = losses[0].min() + F32(0.5)
+    host = [sw.x.copy(), sw.v.copy(), sw.pbest.copy(), sw.pbest_loss.copy(), np.full(D, 3.0, F32)]
+    hgl = np.array([np.inf], F32)
+    dev = [gh.to_dev(a) for a in host]
+    dgl = gh.to_dev(hgl)
+    h = pso.pso_ps_create(K, D, ld)
+    try:
+        pso.pso_ps_set_launch(h, block, 0, 0, 0, False)
+        pso.pso_ps_set_variant(h, fused_rows)
+        reps = []
+        for s in range(3):
+            pso.pso_ps_sync_history(h, dev[0], dev[1], dev[2], dev[3], gh.to_dev(losses[s]), dev[4],
+                                    dgl, 0.7, 1.2, 1.3, 31, s)
+            g, improved, rep = oracle.sync(host[0][:, :D], host[1][:, :D], host[2][:, :D], host[3],
+                                           losses[s], host[4], F32(0.7), F32(1.2), F32(1.3), 31, s,
+                                           gbest_loss=hgl)
+            gg, gi, grep = pso.pso_ps_last_selection(h, K, with_replaced=True)
+            assert (gg, gi, grep) == (g, [bool(t) for t in improved], rep)
+            gh.assert_bits_equal(dgl.cpu().numpy(), hgl, f"single pass history step {s}: gbest_loss")
+            compare_state(dev, host, f"single pass history step {s}")
+            reps.append(rep)
+        assert reps[:2] == [True, False]
+    finally:
+        torch.cuda.synchronize()
+        pso.pso_ps_destroy(h)
+
+
 @pytest.mark.parametrize("K,D,offsets", [
     (5, 20_000, [0, 0, 0, 0, 0]),              # separately allocated rows, all vector path
     (5, 20_002, [0, 2, 0, 2, 2]),              # some rows 8-byte aligned only
