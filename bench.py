@@ -77,7 +77,8 @@ def stream_probe(args) -> int:
                  rows_per_wg=args.probe_rows_per_wg, chunked=args.probe_order == "chunked",
                  super_tiles=args.super_tiles or 1024, chunk_tiles=args.chunk_tiles or 128,
                  wgs_per_cu=args.wgs_per_cu or 10, nt_loads=bool(args.probe_nt_loads),
-                 nt_stores=bool(args.probe_nt_stores))
+                 nt_stores=bool(args.probe_nt_stores),
+                 absolute_chunks=args.probe_absolute_chunks)
 
     def stage(_):
         probes.pso_ps_probe_stream(args.probe_mix, x, v, p, sink, K, D, ld,
@@ -216,6 +217,8 @@ def main() -> int:
     ap.add_argument("--fused-rows", type=int, default=0,
                     help="sync, history: the single-pass kernels with this many rows in flight per "
                          "workgroup (pso_ps_set_variant) instead of the default two kernels")
+    ap.add_argument("--chunk-origin", type=int, default=-1,
+                    help="pso_ps_set_variant's chunk_origin (default: the library's)")
     ap.add_argument("--ld", type=int, default=0,
                     help="row stride in elements (default D, the dense layout of the metric)")
     ap.add_argument("--misalign", default="",
@@ -235,8 +238,10 @@ def main() -> int:
     ap.add_argument("--probe-quads", type=int, default=1)
     ap.add_argument("--probe-nt-loads", type=int, default=1)
     ap.add_argument("--probe-nt-stores", type=int, default=1)
+    ap.add_argument("--probe-absolute-chunks", type=int, default=0)
     ap.add_argument("--graph", action="store_true",
-                    help="sync only: also replay the stages from a HIP graph and report that time")
+                    help="also capture ten stages into a HIP graph, replay it and report the time "
+                         "per stage (roofline.stage.hip_graph_replay_ms)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch one plain device copy of 1 GiB (counter calibration)")
@@ -291,7 +296,9 @@ def main() -> int:
     dloss = torch.from_numpy(sw.losses).to(dev)          # [total, K], resident
     dg = shifted(np.zeros(D, np.float32), offs[3])
     dgl = torch.full((1,), float("inf"), dtype=torch.float32, device=dev)
-    w_tab, c1, c2 = [float(t) for t in sw.w], float(sw.c1), float(sw.c2)
+    # the workload's inertia schedule covers cfg.steps stages; longer runs go round it again
+    w_tab = [float(sw.w[s % cfg.steps]) for s in range(total)]
+    c1, c2 = float(sw.c1), float(sw.c2)
     del sw
 
     h = pso.pso_ps_create(K, D, D, seg_sizes=list(cfg.segments)) if args.variant == "segments" \
@@ -299,25 +306,25 @@ def main() -> int:
     if args.block or args.super_tiles or args.chunk_tiles or args.wgs_per_cu or args.force_generic:
         pso.pso_ps_set_launch(h, args.block, args.super_tiles, args.chunk_tiles, args.wgs_per_cu,
                               args.force_generic)
-    if args.fused_rows:
-        pso.pso_ps_set_variant(h, args.fused_rows)
+    if args.fused_rows or args.chunk_origin >= 0:
+        pso.pso_ps_set_variant(h, args.fused_rows, max(args.chunk_origin, 0))
     stream = torch.cuda.current_stream()
 
-    def stage(s):
+    def stage(s, st=None):
         """One whole synchronization stage through the entry point of the variant."""
+        st = st or stream
         if args.variant == "sync":
-            pso.pso_ps_sync(h, dx, dv, dp, dpl, dloss[s], dg, w_tab[s], c1, c2, cfg.seed, s, stream)
+            pso.pso_ps_sync(h, dx, dv, dp, dpl, dloss[s], dg, w_tab[s], c1, c2, cfg.seed, s, st)
         elif args.variant == "history":
             pso.pso_ps_sync_history(h, dx, dv, dp, dpl, dloss[s], dg, dgl, w_tab[s], c1, c2,
-                                    cfg.seed, s, stream)
+                                    cfg.seed, s, st)
         elif args.variant == "rows":
-            pso.pso_ps_sync_rows(h, xr, vr, pr, dpl, dloss[s], dg, w_tab[s], c1, c2, cfg.seed, s,
-                                 stream)
+            pso.pso_ps_sync_rows(h, xr, vr, pr, dpl, dloss[s], dg, w_tab[s], c1, c2, cfg.seed, s, st)
         elif args.variant == "segments":
             pso.pso_ps_sync_segments(h, xs, vs, ps, dpl, dloss[s], gs, w_tab[s], c1, c2,
-                                     cfg.seed, s, stream)
+                                     cfg.seed, s, st)
         else:
-            pso.pso_ps_average(h, dx, dg, stream)
+            pso.pso_ps_average(h, dx, dg, st)
 
     # -- the timed region: K whole stages through the entry point ---------------------------
     for s in range(args.warmup):
@@ -347,16 +354,14 @@ def main() -> int:
 
     # -- optional: the same stages replayed from a HIP graph --------------------------------
     graph_ms = None
-    if args.graph and args.variant == "sync":
+    if args.graph:
         per_graph = min(args.steps, 10)
         side = torch.cuda.Stream()
         side.wait_stream(stream)
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph, stream=side):
             for k in range(per_graph):
-                s = args.warmup + k
-                pso.pso_ps_sync(h, dx, dv, dp, dpl, dloss[s], dg, w_tab[s], c1, c2, cfg.seed, s,
-                                side)
+                stage(args.warmup + k, side)
         graph.replay()
         torch.cuda.synchronize()
         replays = max(1, args.steps // per_graph)

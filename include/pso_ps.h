@@ -237,8 +237,14 @@ int pso_ps_set_launch(pso_ps_ctx* h, int block_threads, int super_tiles, int chu
  *                   has the loads of P particles in flight (block_threads 64,
  *                   128 or 256).  Moves the fewest bytes; kept for measurement,
  *                   see the kernel's comment for when it is slower.
- * The other entry points ignore it. */
-int pso_ps_set_variant(pso_ps_ctx* h, int fused_rows);
+ *   chunk_origin    where the runs of chunk_tiles consecutive tiles that an XCD
+ *                   is handed start in the update pass of the flat layout:
+ *                   0 counted from each row's first tile; 1 at absolute
+ *                   multiples of the run size in memory, run j of memory going
+ *                   to XCD j mod 8; 2 at absolute multiples of the run size,
+ *                   the first run of every row going to XCD 0.
+ * The other entry points ignore both. */
+int pso_ps_set_variant(pso_ps_ctx* h, int fused_rows, int chunk_origin);
 
 /* hipError_t (as int) of the last failed HIP call on this handle, 0 if none. */
 int pso_ps_last_hip_error(const pso_ps_ctx* h);

@@ -31,13 +31,21 @@ extern "C" {
  *   wgs_per_cu   cap on resident workgroups per compute unit (3..63), by an LDS
  *                reservation that is never touched; other values: no cap
  *   nt_loads, nt_stores  != 0: non-temporal accesses
+ *   absolute_chunks  chunked only.  0: the runs of chunk_tiles tiles handed to an
+ *                XCD are counted from each row's first tile.  1: they start at
+ *                absolute multiples of their size in memory and go to XCD
+ *                (address / run size) mod 8, so the same columns of different
+ *                rows go to different XCDs.  2: they start at absolute
+ *                multiples of their size, but the first run of every row goes
+ *                to XCD 0, so the columns of an XCD shift by less than one run
+ *                from row to row
  * The arrays must be 16-byte aligned and ld a multiple of 4 (K > 1); the first
  * and last partial 16 bytes of a row are skipped.
  * Returns 0, -1 (bad argument), -2 (alignment) or -3 (launch failed). */
 int pso_ps_probe_stream(int mix, float* x, float* v, float* pbest, float* sink, int K,
                         int64_t D, int64_t ld, int block_threads, int quads, int rows_per_wg,
                         int chunked, int super_tiles, int chunk_tiles, int wgs_per_cu,
-                        int nt_loads, int nt_stores, void* hip_stream);
+                        int nt_loads, int nt_stores, int absolute_chunks, void* hip_stream);
 
 #ifdef __cplusplus
 }

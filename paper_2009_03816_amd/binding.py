@@ -95,7 +95,7 @@ def load():
     lib.pso_ps_schedule.argtypes = [I64, I64, I64, I64, F, F, F, F, ctypes.POINTER(I),
                                     ctypes.POINTER(F), ctypes.POINTER(F), ctypes.POINTER(F)]
     lib.pso_ps_set_launch.argtypes = [P, I, I, I, I, I]
-    lib.pso_ps_set_variant.argtypes = [P, I]
+    lib.pso_ps_set_variant.argtypes = [P, I, I]
     lib.pso_ps_last_hip_error.argtypes = [P]
     lib.pso_ps_destroy.argtypes = [P]
     lib.pso_ps_strerror.argtypes = [I]
@@ -263,8 +263,8 @@ def pso_ps_set_launch(h: int, block_threads: int = 0, super_tiles: int = 0, chun
                                     int(force_generic)), "pso_ps_set_launch", h)
 
 
-def pso_ps_set_variant(h: int, fused_rows: int = 0) -> None:
-    _check(load().pso_ps_set_variant(h, fused_rows), "pso_ps_set_variant", h)
+def pso_ps_set_variant(h: int, fused_rows: int = 0, chunk_origin: int = 0) -> None:
+    _check(load().pso_ps_set_variant(h, fused_rows, chunk_origin), "pso_ps_set_variant", h)
 
 
 def pso_ps_source_hash() -> str:

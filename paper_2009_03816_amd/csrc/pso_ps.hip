@@ -294,6 +294,27 @@ __device__ __forceinline__ void update_tile(const RowPtrs& r, const float* __res
     }
 }
 
+// Where the runs of consecutive tiles handed to an XCD (2^chunk_log2 tiles) start.
+// origin 0: counted from the row's first tile.  Otherwise at absolute multiples
+// of the run's size in memory: the decoded tile index then counts from the
+// last such multiple (origin 2) or the last multiple of eight runs (origin 1)
+// at or below the row's first tile, and indices before the row's first tile
+// name no tile.  With origin 1 a run goes to XCD (address / run size) mod 8, so
+// the same columns of different rows go to different XCDs; with origin 2 the
+// first run of every row goes to XCD 0 and the columns of an XCD shift by less
+// than one run from row to row.
+template <int BLOCK>
+__device__ __forceinline__ bool tile_from_origin(const float* row_x, const TileOrder& ord,
+                                                 int origin, unsigned* tile) {
+    if (origin == 0) return true;
+    const unsigned cycle = (origin == 2 ? 1u : 8u) << ord.chunk_log2;
+    const unsigned first =
+        (unsigned)((reinterpret_cast<uintptr_t>(row_x) / (BLOCK * 16u)) & (uintptr_t)(cycle - 1u));
+    if (*tile < first) return false;
+    *tile -= first;
+    return true;
+}
+
 // Update pass over stacked [K, ld] arrays.  gbest_loss (may be null) is the
 // caller's historical-gBest loss: the selection kernel only reads it, and the
 // value that belongs to this stage is stored here, after that kernel is done.
@@ -301,12 +322,13 @@ template <int BLOCK, bool VEC>
 __global__ __launch_bounds__(BLOCK) void update_kernel(ColumnBlock b, int K,
                                                        const Selection* __restrict__ sel,
                                                        MoveParams m, TileOrder ord,
-                                                       float* gbest_loss) {
+                                                       float* gbest_loss, int origin) {
     if (gbest_loss && blockIdx.x == 0 && threadIdx.x == 0) *gbest_loss = sel->gbest_loss;
     unsigned i, tile;
     if (!decode_tile_order(ord, (unsigned)K, blockIdx.x, &i, &tile)) return;
     const long long row = (long long)i * b.ld;
     const RowPtrs r{b.x + row, b.v + row, b.pbest + row};
+    if (VEC && !tile_from_origin<BLOCK>(r.x, ord, origin, &tile)) return;
     update_tile<BLOCK, VEC>(r, b.gbest, b.n, b.d0, i, tile, is_improved(sel, (int)i), m);
 }
 
@@ -727,6 +749,7 @@ struct pso_ps_ctx {
     int wgs_per_cu;        // 0 = default; else cap on resident update workgroups per compute unit
     bool force_generic;
     int fused_rows;        // 0: selection/copy kernel + update kernel; P > 0: single pass, P rows in flight
+    int chunk_origin;      // 0, 1, 2: see tile_from_origin
     bool eight_xcds;       // 256 compute units: the chip is driven as one device of 8 XCDs
     int last_hip_error;
 };
@@ -810,6 +833,20 @@ bool plan_order(const pso_ps_ctx* h, int rows, unsigned long long tiles, unsigne
     return plan_tile_order(rows, tiles, super, chunk, ord, grid);
 }
 
+// Tile indices that name no tile when runs start at absolute addresses: the
+// row that starts furthest into its run (or its eight runs) needs that many more.
+unsigned long long origin_slack(const pso_ps_ctx* h, unsigned tile) {
+    if (h->chunk_origin == 0 || !h->eight_xcds) return 0;
+    unsigned long long super = h->super_tiles ? (unsigned long long)h->super_tiles
+                                              : kDefaultSuperBytes / (tile * 4u);
+    unsigned long long chunk = h->chunk_tiles ? (unsigned long long)h->chunk_tiles
+                                              : kDefaultChunkBytes / (tile * 4u);
+    if (chunk > super) chunk = super;
+    if (chunk < 1) chunk = 1;
+    const unsigned long long run = 1ull << tile_order_ceil_log2(chunk);
+    return (h->chunk_origin == 2 ? run : 8ull * run) - 1ull;
+}
+
 // Dynamic LDS requested for a streaming launch.  The kernels never touch it:
 // the reservation only caps how many workgroups a compute unit holds at once
 // (160 KiB of LDS per compute unit), which is what the memory system likes.
@@ -860,16 +897,18 @@ hipError_t launch_update(const pso_ps_ctx* h, const ColumnBlock& b, const MovePa
     const bool vec = vector_path(h);
     TileOrder ord;
     unsigned long long grid = 0;
-    const unsigned long long tiles = tiles_per_row(
-        h->K, b.n, vec, BLOCK * 4u, [&](int i) { return b.x + (long long)i * b.ld; });
+    const unsigned long long tiles =
+        tiles_per_row(h->K, b.n, vec, BLOCK * 4u, [&](int i) { return b.x + (long long)i * b.ld; }) +
+        (vec ? origin_slack(h, BLOCK * 4u) : 0ull);
     if (!plan_order(h, h->K, tiles, BLOCK * 4u, &ord, &grid)) return hipErrorInvalidConfiguration;
     const unsigned lds = occupancy_cap_lds(h, BLOCK);
     if (vec)
         hipLaunchKernelGGL((update_kernel<BLOCK, true>), dim3((unsigned)grid), dim3(BLOCK), lds,
-                           stream, b, h->K, (const Selection*)h->sel, m, ord, gbest_loss);
+                           stream, b, h->K, (const Selection*)h->sel, m, ord, gbest_loss,
+                           h->chunk_origin);
     else
         hipLaunchKernelGGL((update_kernel<BLOCK, false>), dim3((unsigned)grid), dim3(BLOCK), lds,
-                           stream, b, h->K, (const Selection*)h->sel, m, ord, gbest_loss);
+                           stream, b, h->K, (const Selection*)h->sel, m, ord, gbest_loss, 0);
     return hipGetLastError();
 }
 
@@ -1247,7 +1286,7 @@ int pso_ps_create(pso_ps_ctx** out, int K, int64_t D, int64_t ld, int n_seg,
     h->sel_bytes = sizeof(Selection) + (size_t)(h->mask_words - 1) * sizeof(uint64_t);
     h->sel = nullptr; h->last_stream = nullptr; h->have_selection = false;
     h->block_threads = 0; h->super_tiles = 0; h->chunk_tiles = 0; h->wgs_per_cu = 0;
-    h->force_generic = false; h->fused_rows = 0; h->eight_xcds = true; h->last_hip_error = 0;
+    h->force_generic = false; h->fused_rows = 0; h->chunk_origin = 0; h->eight_xcds = true; h->last_hip_error = 0;
 
     DeviceScope scope(device);
     hipError_t e = scope.err;
@@ -1331,7 +1370,7 @@ int pso_ps_sync_static(int device, int K, int64_t D, int64_t ld, float* x, float
     h.sel_bytes = sizeof(Selection) + (size_t)(h.mask_words - 1) * sizeof(uint64_t);
     h.last_stream = nullptr; h.have_selection = false;
     h.block_threads = 0; h.super_tiles = 0; h.chunk_tiles = 0; h.wgs_per_cu = 0;
-    h.force_generic = false; h.fused_rows = 0; h.eight_xcds = dev.eight_xcds; h.last_hip_error = 0;
+    h.force_generic = false; h.fused_rows = 0; h.chunk_origin = 0; h.eight_xcds = dev.eight_xcds; h.last_hip_error = 0;
     return sync_flat(&h, x, v, pbest, pbest_loss, loss, gbest, nullptr,
                      make_params(w, c1, c2, seed, step), (hipStream_t)hip_stream);
 }
@@ -1470,13 +1509,14 @@ int pso_ps_set_launch(pso_ps_ctx* h, int block_threads, int super_tiles, int chu
     return PSO_PS_OK;
 }
 
-int pso_ps_set_variant(pso_ps_ctx* h, int fused_rows) {
-    if (!h) return PSO_PS_EINVAL;
+int pso_ps_set_variant(pso_ps_ctx* h, int fused_rows, int chunk_origin) {
+    if (!h || chunk_origin < 0 || chunk_origin > 2) return PSO_PS_EINVAL;
     switch (fused_rows) {
         case 0: case 1: case 2: case 3: case 4: case 6: case 8: break;
         default: return PSO_PS_EINVAL;
     }
     h->fused_rows = fused_rows;
+    h->chunk_origin = chunk_origin;
     return PSO_PS_OK;
 }
 

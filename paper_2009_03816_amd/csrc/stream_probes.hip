@@ -32,6 +32,7 @@ struct StreamArgs {
     int rows;          // K
     int rows_per_wg;   // R: a workgroup walks R consecutive rows of its tile
     int chunked;       // 1: XCD-aware order (TileOrder), 0: plain row-major
+    int absolute;      // chunked only: chunk borders at absolute addresses, not counted from the row start
     TileOrder ord;
 };
 
@@ -66,7 +67,16 @@ __global__ __launch_bounds__(BLOCK) void stream_kernel(StreamArgs a, float* sink
         float* v = a.v + i * a.ld;
         float* p = a.p + i * a.ld;
         const long long phase = (long long)((reinterpret_cast<uintptr_t>(x) >> 2) & (TILE - 1u));
-        const long long c0 = (long long)tile * TILE - phase + 4 * (long long)threadIdx.x;
+        long long t = tile;
+        if (a.absolute) {
+            // `tile` counts from the last multiple of eight chunks (absolute 2: of
+            // one chunk) at or below the row's first tile; tiles before the row's
+            // first one do not exist
+            const unsigned long long cycle = (a.absolute == 2 ? 1ull : 8ull) << a.ord.chunk_log2;
+            t -= (long long)((reinterpret_cast<uintptr_t>(x) / (TILE * 4u)) % cycle);
+            if (t < 0) continue;
+        }
+        const long long c0 = t * TILE - phase + 4 * (long long)threadIdx.x;
         f32x4 xq[QUADS], vq[QUADS], pq[QUADS];
         bool ok[QUADS];
 #pragma unroll
@@ -122,9 +132,11 @@ hipError_t launch_mix(int mix, int ntl, int nts, dim3 grid, unsigned lds, hipStr
 extern "C" int pso_ps_probe_stream(int mix, float* x, float* v, float* pbest, float* sink, int K,
                                    int64_t D, int64_t ld, int block_threads, int quads,
                                    int rows_per_wg, int chunked, int super_tiles, int chunk_tiles,
-                                   int wgs_per_cu, int nt_loads, int nt_stores, void* hip_stream) {
+                                   int wgs_per_cu, int nt_loads, int nt_stores, int absolute_chunks,
+                                   void* hip_stream) {
     if (!x || !v || !pbest || !sink || K < 1 || D < 4 || ld < D || rows_per_wg < 1) return -1;
     if (mix < 0 || mix > 2 || (quads != 1 && quads != 2)) return -1;
+    if (absolute_chunks < 0 || absolute_chunks > 2) return -1;
     if (block_threads != 64 && block_threads != 128 && block_threads != 256) return -1;
     if (super_tiles < 1 || chunk_tiles < 1 || (super_tiles & (super_tiles - 1)) ||
         (chunk_tiles & (chunk_tiles - 1)))
@@ -133,14 +145,20 @@ extern "C" int pso_ps_probe_stream(int mix, float* x, float* v, float* pbest, fl
          reinterpret_cast<uintptr_t>(pbest)) & 15u)
         return -2;
     if (K > 1 && (ld & 3)) return -2;
-    StreamArgs a{x, v, pbest, (long long)ld, (long long)D, K, rows_per_wg, chunked ? 1 : 0, {}};
+    StreamArgs a{x, v, pbest, (long long)ld, (long long)D, K, rows_per_wg, chunked ? 1 : 0,
+                 chunked ? absolute_chunks : 0, {}};
     const unsigned tile = (unsigned)block_threads * 4u * (unsigned)quads;
     unsigned long long max_phase = 0;
     for (int i = 0; i < K; ++i) {
         const unsigned long long ph = (reinterpret_cast<uintptr_t>(x + (long long)i * ld) >> 2) & (tile - 1u);
         if (ph > max_phase) max_phase = ph;
     }
-    const unsigned long long tiles = (max_phase + (unsigned long long)D + tile - 1) / tile;
+    unsigned long long tiles = (max_phase + (unsigned long long)D + tile - 1) / tile;
+    if (a.absolute) {  // room for the row that starts furthest into its cycle of eight chunks
+        unsigned long long chunk = 1;
+        while (chunk < (unsigned long long)(chunk_tiles < super_tiles ? chunk_tiles : super_tiles)) chunk <<= 1;
+        tiles += 8ull * chunk - 1;
+    }
     const int groups = (K + rows_per_wg - 1) / rows_per_wg;
     unsigned long long grid = 0;
     if (!plan_tile_order(groups, tiles, (unsigned long long)super_tiles, (unsigned long long)chunk_tiles,

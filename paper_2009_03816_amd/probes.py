@@ -20,7 +20,7 @@ def load():
         import torch  # noqa: F401  (the HIP runtime torch loaded serves this library too)
         lib = ctypes.CDLL(_build.PROBES_LIBRARY)
         P, I, I64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
-        lib.pso_ps_probe_stream.argtypes = [I, P, P, P, P, I, I64, I64, I, I, I, I, I, I, I, I, I, P]
+        lib.pso_ps_probe_stream.argtypes = [I, P, P, P, P, I, I64, I64, I, I, I, I, I, I, I, I, I, I, P]
         lib.pso_ps_probe_stream.restype = I
         _lib = lib
     return _lib
@@ -32,10 +32,12 @@ MIXES = {"read": 0, "copy": 1, "inplace": 2}
 def pso_ps_probe_stream(mix: str, x, v, pbest, sink, K: int, D: int, ld: int, block_threads: int = 128,
                         quads: int = 1, rows_per_wg: int = 1, chunked: bool = True,
                         super_tiles: int = 1024, chunk_tiles: int = 128, wgs_per_cu: int = 10,
-                        nt_loads: bool = True, nt_stores: bool = True, stream: int = 0) -> None:
+                        nt_loads: bool = True, nt_stores: bool = True,
+                        absolute_chunks: int = 0, stream: int = 0) -> None:
     rc = load().pso_ps_probe_stream(MIXES[mix], x.data_ptr(), v.data_ptr(), pbest.data_ptr(),
                                     sink.data_ptr(), K, D, ld, block_threads, quads, rows_per_wg,
                                     int(chunked), super_tiles, chunk_tiles, wgs_per_cu,
-                                    int(nt_loads), int(nt_stores), stream or None)
+                                    int(nt_loads), int(nt_stores), int(absolute_chunks),
+                                    stream or None)
     if rc != 0:
         raise RuntimeError(f"pso_ps_probe_stream: status {rc}")

@@ -59,4 +59,4 @@ def test_probe_library_exports_what_its_header_declares():
         assert hasattr(lib, name), name
     # rejected before any HIP call is made
     assert lib.pso_ps_probe_stream(2, None, None, None, None, 4, 16, 16, 128, 1, 1, 1, 1024, 128,
-                                   10, 1, 1, None) == -1
+                                   10, 1, 1, 0, None) == -1

@@ -141,6 +141,20 @@ def test_launch_shape_does_not_change_bits(oracle, block, sup, chunk, wgs, gener
                    wgs_per_cu=wgs, force_generic=generic)
 
 
+@pytest.mark.parametrize("origin", [1, 2])
+@pytest.mark.parametrize("block,sup,chunk,offset,ld", [
+    (64, 0, 0, 0, 70_002), (64, 8, 2, (3, 1, 2, 0), 70_003), (128, 4, 4, 258, 70_002),
+    (256, 16, 1, (32, 0, 0, 0), 70_006), (64, 2, 1, 1, 70_002), (1024, 2, 2, 0, 70_002)])
+def test_chunk_origin_does_not_change_bits(oracle, origin, block, sup, chunk, offset, ld):
+    """Runs of tiles that start at absolute addresses: rows begin in the middle
+    of a run, some workgroups name no tile."""
+    print(f"[case] chunk origin {origin} block={block} super={sup} chunk={chunk} offset={offset} "
+          f"ld={ld}", flush=True)
+    sw = wl.small_swarm(9, 70_002, seed=6, ld=ld, steps=2)
+    run_trajectory(oracle, sw, steps=2, offset=offset, block_threads=block, super_tiles=sup,
+                   chunk_tiles=chunk, chunk_origin=origin)
+
+
 def test_ties_nan_and_inf_losses(oracle):
     K, D = 8, 5000
     print(f"[case] ties / NaN / inf losses K={K} D={D}", flush=True)
