@@ -73,10 +73,16 @@ def stream_probe(args) -> int:
     sink = torch.zeros(1, dtype=torch.float32, device=dev)
     keep = x[:, :4096].clone()
     stream = torch.cuda.current_stream()
-    shape = dict(block_threads=args.block or 128, quads=args.probe_quads,
+    # defaults: the launch shape of the update pass (64 threads, runs of 256 KiB, super-chunks
+    # of 2 MiB, about 20 wavefronts per compute unit)
+    block = args.block or 64
+    tile_bytes = block * 16 * args.probe_quads
+    shape = dict(block_threads=block, quads=args.probe_quads,
                  rows_per_wg=args.probe_rows_per_wg, chunked=args.probe_order == "chunked",
-                 super_tiles=args.super_tiles or 1024, chunk_tiles=args.chunk_tiles or 128,
-                 wgs_per_cu=args.wgs_per_cu or 10, nt_loads=bool(args.probe_nt_loads),
+                 super_tiles=args.super_tiles or (2 << 20) // tile_bytes,
+                 chunk_tiles=args.chunk_tiles or (256 << 10) // tile_bytes,
+                 wgs_per_cu=args.wgs_per_cu or max(3, 20 * 64 // block),
+                 nt_loads=bool(args.probe_nt_loads),
                  nt_stores=bool(args.probe_nt_stores),
                  absolute_chunks=args.probe_absolute_chunks)
 
