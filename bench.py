@@ -30,16 +30,44 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 # size), keyed by workload and by the hash of the kernel source they were taken
 # with: a changed kernel reports null until the counters are taken again.
 MEASURED_TRAFFIC = {
-    # profiles/update_kernel_resnet50x32_hbm_traffic.md: mean of three timed launches
-    ("resnet50x32", "75be0b27336ea88a"): 16460299000.0,
+    # profiles/update_kernel_resnet50x32_hbm_traffic.md: mean of the three timed launches
+    ("resnet50x32", "04d204538cee46f9"): 16459783000.0,
 }
 
-# What plain streams reach on MI355X with the access mix of the update pass
-# (profiles/stream_ceilings_resnet50x32.md); quoted next to the roofline fraction
-# as the practical ceiling under the 8 TB/s peak.  Stored, not measured in this run.
+# What arithmetic-free streams over the same kind of arrays reached on one MI355X
+# (profiles/ceilings_and_rejected_variants_resnet50x32.md, a box of the slower kind): the
+# practical ceilings under the 8 TB/s peak.  Stored figures of another run; the in-place
+# stream is also measured live on this run's own arrays (roofline.stream_ceiling.same_box).
 STREAM_CEILING = {
-    "in_place_3_reads_2_writes_GBps": 6650.0, "read_only_GBps": 7060.0, "copy_1r1w_GBps": 6600.0,
-    "source": "profiles/stream_ceilings_resnet50x32.md (stored figures, another run)"}
+    "in_place_3_reads_2_writes_GBps": 6380.0, "read_only_GBps": 7400.0, "copy_1r1w_GBps": 6590.0,
+    "source": "profiles/ceilings_and_rejected_variants_resnet50x32.md (stored figures, another run)"}
+
+
+def same_box_ceiling(torch, x, v, p, K, D, ld, stream):
+    """The in-place 3-reads-2-writes stream of the probes library over this run's own x, v,
+    pbest (written back unchanged), in the update pass's launch shape: GB/s, or None if the
+    probes library is missing or the arrays are not 16-byte aligned."""
+    try:
+        from paper_2009_03816_amd import probes
+        probes.load()
+    except Exception:
+        return None
+    if any(t.data_ptr() % 16 for t in (x, v, p)) or (K > 1 and ld % 4):
+        return None
+    sink = torch.zeros(1, dtype=torch.float32, device=x.device)
+    shape = dict(block_threads=64, quads=1, rows_per_wg=1, chunked=True, super_tiles=2048,
+                 chunk_tiles=256, wgs_per_cu=20, nt_loads=True, nt_stores=True)
+    run = lambda: probes.pso_ps_probe_stream("inplace", x, v, p, sink, K, D, ld,
+                                             stream=int(stream.cuda_stream), **shape)
+    for _ in range(2):
+        run()
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    marks[0].record(stream)
+    for _ in range(10):
+        run()
+    marks[1].record(stream)
+    torch.cuda.synchronize()
+    return 10 * 20.0 * K * D / (marks[0].elapsed_time(marks[1]) * 1e-3) / 1e9
 
 
 def kernel_source_hash() -> str:
@@ -456,7 +484,13 @@ def main() -> int:
                     "algorithmic_bytes_per_launch": stage_bytes, "kernel_ms_avg": stage_t["avg"],
                     "kernel_ms_median": stage_t["median"], "kernel_ms_min": stage_t["min"],
                     "stage": stage_roof}
-    roofline["stream_ceiling"] = STREAM_CEILING
+    roofline["stream_ceiling"] = dict(STREAM_CEILING)
+    if args.variant in ("sync", "history"):
+        live = same_box_ceiling(torch, dx, dv, dp, K, D, ld, stream)
+        roofline["stream_ceiling"]["same_box"] = {
+            "in_place_3_reads_2_writes_GBps": live,
+            "what": "arithmetic-free stream over this run's x, v, pbest in the update pass's "
+                    "launch shape, measured after the timed stages"}
     roofline["torch_copy_GBps_same_box"] = copy_gbs
     if graph_ms is not None:
         roofline["stage"]["hip_graph_replay_ms"] = graph_ms
