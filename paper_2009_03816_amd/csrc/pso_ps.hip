@@ -9,9 +9,12 @@
 //                        copy, Eq. (6) velocity and Eq. (7) position update.
 // The same two steps exist for K separate row arrays (update_rows_kernel, the
 // gbest copy with a TableSource) and for ragged per-tensor segments, 32 per
-// launch (select_gbest_segments_kernel, update_segments_kernel).  Parameter
-// averaging, the synchronization the method replaces, is mean_kernel +
-// broadcast_kernel.
+// launch (select_gbest_segments_kernel, update_segments_kernel), each also with
+// the historical gBest of Section II-C.  Parameter averaging, the
+// synchronization the method replaces, is mean_kernel + broadcast_kernel.
+// fused_rows_kernel is the stage as a single pass (one workgroup owns a tile of
+// columns for all K rows and keeps its piece of gbest on chip): the fewest
+// bytes, but slower on this chip; kept selectable for measurement.
 //
 // The update pass is bound by HBM traffic, not by arithmetic: per particle
 // parameter it must read x and v, write x and v, and either read pbest (not
@@ -20,21 +23,23 @@
 // (read x_g, write gbest, first read of gbest by the update pass); the other
 // K-1 reads of a gbest tile are served by the caches.
 //
-// Mapping of the update pass: one workgroup = one row (particle) x one tile of
-// BLOCK*4 consecutive floats, one 128-bit access per thread and array, i.e. the
-// access pattern of a plain streaming copy.  What makes it reach copy-like
-// bandwidth on this chip:
-//   * tiles are aligned to the ADDRESS of the row (not to column 0), so every
-//     wavefront touches whole 128-byte lines even when the row stride is not a
-//     multiple of the tile (D = 25,557,032 gives rows 160 bytes off a 4 KiB
-//     boundary); the ragged head and tail of a row are handled element-wise;
+// Mapping of the update pass: one workgroup = one wavefront = one row
+// (particle) x one tile of 256 consecutive floats, one 128-bit access per
+// thread and array, i.e. the access pattern of a plain streaming copy.  What
+// makes it reach copy-like bandwidth on this chip:
+//   * tiles are aligned to the ADDRESS of the row's x (not to column 0), so
+//     every wavefront touches whole 128-byte lines even when the row stride is
+//     not a multiple of the tile (D = 25,557,032 gives rows 160 bytes off a
+//     4 KiB boundary); the ragged head and tail of a row are handled
+//     element-wise; v and pbest may sit at any 4-byte alignment and a row may
+//     start at an odd flat index (three Philox calls per four columns then);
 //   * x, v, pbest use non-temporal accesses (each byte is touched once); gbest
 //     uses ordinary cached loads so that it stays resident;
 //   * the workgroup order is XCD-aware: workgroup b runs on XCD b % 8, each XCD
-//     is given chunks of consecutive tiles and walks a "super-chunk" of its
-//     tiles for row 0, 1, .., K-1 before moving on, so that a gbest tile is
-//     re-read from the XCD's own L2 and the DRAM pages of few rows are open at
-//     a time;
+//     is given runs of consecutive tiles (256 KiB) and walks a "super-chunk"
+//     (2 MiB) of its tiles for row 0, 1, .., K-1 before moving on, so that a
+//     gbest tile is re-read from the XCD's own L2 and the DRAM pages of few
+//     rows are open at a time;
 //   * the Philox rounds are placed between the loads and their first use;
 //   * each launch reserves LDS it never touches, which caps a compute unit at
 //     about 20 resident wavefronts of the 32 it could hold: HBM serves fewer,
@@ -668,29 +673,49 @@ __global__ __launch_bounds__(BLOCK) void fused_rows_kernel(ColumnBlock b, int K,
 // Reading K rows at one column is tolerant of the rows' different alignments.
 // Column tiles are dealt to the XCDs in chunks like those of the update pass
 // (`ord` is an order for a single row of column tiles).
-template <int BLOCK>
-__global__ __launch_bounds__(BLOCK) void mean_kernel(const float* __restrict__ x,
-                                                     float* __restrict__ mean, long long ld,
-                                                     long long n, int K, TileOrder ord) {
+constexpr int kMeanBlock = 256;
+constexpr int kMeanQuads = 1;  // 128-bit groups per thread and row, kMeanBlock groups apart
+                               // (2, 4 and 8 measured no faster: 1.06, 1.08, 1.05 against 1.05 ms)
+constexpr unsigned kMeanTile = kMeanBlock * 4 * kMeanQuads;
+
+__global__ __launch_bounds__(kMeanBlock) void mean_kernel(const float* __restrict__ x,
+                                                          float* __restrict__ mean, long long ld,
+                                                          long long n, int K, TileOrder ord) {
     unsigned row, tile;
     if (!decode_tile_order(ord, 1u, blockIdx.x, &row, &tile)) return;
-    const long long c = ((long long)tile * BLOCK + threadIdx.x) * 4;
-    if (c >= n) return;
+    const long long c0 = (long long)tile * kMeanTile + 4 * (long long)threadIdx.x;
     const float kf = (float)K;
-    if (c + 4 <= n) {
-        // (issuing several rows' loads before the first add changes nothing: the
-        // pass is bound by the K rows it has open at once, not by latency)
-        f32x4 sum = __builtin_nontemporal_load(reinterpret_cast<const f32x4_a4*>(x + c));
-        for (int k = 1; k < K; ++k)
-            sum = sum + __builtin_nontemporal_load(
-                            reinterpret_cast<const f32x4_a4*>(x + (long long)k * ld + c));
-        *reinterpret_cast<f32x4_a4*>(mean + c) =
-            f32x4{sum.x / kf, sum.y / kf, sum.z / kf, sum.w / kf};
-    } else {
-        for (long long e = c; e < n; ++e) {
-            float sum = x[e];
-            for (int k = 1; k < K; ++k) sum = sum + x[(long long)k * ld + e];
-            mean[e] = sum / kf;
+    f32x4 sum[kMeanQuads];
+    bool whole[kMeanQuads];
+#pragma unroll
+    for (int u = 0; u < kMeanQuads; ++u) {
+        const long long c = c0 + (long long)u * (kMeanBlock * 4);
+        whole[u] = c + 4 <= n;
+        if (whole[u]) sum[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4_a4*>(x + c));
+    }
+    // (issuing several rows' loads before the first add changes nothing: the
+    // pass is bound by the K rows it has open at once, not by latency)
+    for (int k = 1; k < K; ++k) {
+#pragma unroll
+        for (int u = 0; u < kMeanQuads; ++u) {
+            const long long c = c0 + (long long)u * (kMeanBlock * 4);
+            if (whole[u])
+                sum[u] = sum[u] + __builtin_nontemporal_load(
+                                      reinterpret_cast<const f32x4_a4*>(x + (long long)k * ld + c));
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < kMeanQuads; ++u) {
+        const long long c = c0 + (long long)u * (kMeanBlock * 4);
+        if (whole[u]) {
+            *reinterpret_cast<f32x4_a4*>(mean + c) =
+                f32x4{sum[u].x / kf, sum[u].y / kf, sum[u].z / kf, sum[u].w / kf};
+        } else {
+            for (long long e = c; e < n && e < c + 4; ++e) {   // the ragged last columns
+                float s1 = x[e];
+                for (int k = 1; k < K; ++k) s1 = s1 + x[(long long)k * ld + e];
+                mean[e] = s1 / kf;
+            }
         }
     }
 }
@@ -1416,13 +1441,13 @@ int pso_ps_average(pso_ps_ctx* h, float* x, float* mean, void* hip_stream) {
     const hipStream_t stream = (hipStream_t)hip_stream;
     const long long n = (long long)h->D;
     const long long ld = (long long)h->ld;
-    const long long blocks = (n + 4LL * kCopyBlock - 1) / (4LL * kCopyBlock);
+    const long long blocks = (n + (long long)kMeanTile - 1) / (long long)kMeanTile;
     TileOrder mean_ord;
     unsigned long long mean_grid = 0;
-    if (!plan_order(h, 1, (unsigned long long)blocks, kCopyBlock * 4u, &mean_ord, &mean_grid))
+    if (!plan_order(h, 1, (unsigned long long)blocks, kMeanTile, &mean_ord, &mean_grid))
         return hip_fail(h, hipErrorInvalidConfiguration);
-    hipLaunchKernelGGL(mean_kernel<kCopyBlock>, dim3((unsigned)mean_grid), dim3(kCopyBlock), 0,
-                       stream, (const float*)x, mean, ld, n, h->K, mean_ord);
+    hipLaunchKernelGGL(mean_kernel, dim3((unsigned)mean_grid), dim3(kMeanBlock), 0, stream,
+                       (const float*)x, mean, ld, n, h->K, mean_ord);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(h, e);
     // Tiles are aligned to each row's own address, so any 4-byte aligned row

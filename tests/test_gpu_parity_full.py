@@ -217,8 +217,9 @@ def test_rows_longer_than_2_to_31_columns(oracle):
     """Maximum sizes: two rows of 2^31 + 5,242,886 columns each (8.6 GB per row),
     so that column indices, byte offsets and the flat coordinate of the random
     numbers all pass 32 bits.  Inputs are drawn on the device (seeded); the
-    oracle advances windows at the start, across column 2^30 (byte offset 2^32),
-    across column 2^31, and at the ragged end."""
+    oracle advances the whole state through the first stage (every element is
+    compared) and, through all three stages, windows at the start, across column
+    2^30 (byte offset 2^32), across column 2^31, and at the ragged end."""
     K, D = 2, (1 << 31) + 5 * (1 << 20) + 6
     seed, c1, c2, w = 11, 1.3, 1.6, 0.6
     print(f"[case] long rows: K={K} D={D}", flush=True)
@@ -234,6 +235,11 @@ def test_rows_longer_than_2_to_31_columns(oracle):
             (D - 2503, D)]
     host = [[t[:, lo:hi].cpu().numpy().copy() for t in (dx, dv, dp)] for lo, hi in wins]
     hpl = [np.full(K, np.inf, F32) for _ in wins]
+    # the first stage is also compared on every one of the 4.3 G elements
+    whole = [dx.cpu().numpy(), dv.cpu().numpy()]
+    whole.append(whole[0].copy())
+    whole_pl, whole_g = np.full(K, np.inf, F32), np.empty(D, F32)
+    print("[case] long rows: whole state on the host", flush=True)
     dpl = gh.to_dev(np.full(K, np.inf, F32))
     losses = np.array([[0.9, 0.4], [0.7, 0.5], [0.2, 0.6]], F32)   # g = 1, 1, 0; 2, 1, 1 rows improve
     h = pso.pso_ps_create(K, D)
@@ -252,6 +258,17 @@ def test_rows_longer_than_2_to_31_columns(oracle):
                 gh.assert_bits_equal(dp[:, lo:hi].cpu().numpy(), hp, what + ": pbest")
                 gh.assert_close(dx[:, lo:hi].cpu().numpy(), hx, what + ": x")
                 gh.assert_close(dv[:, lo:hi].cpu().numpy(), hv, what + ": v")
+            if s == 0:
+                g, improved = gh.oracle_sync_whole(oracle, whole[0], whole[1], whole[2], whole_pl,
+                                                   losses[0], whole_g, w, c1, c2, seed, 0)
+                assert g_dev == g and imp_dev == [bool(t) for t in improved]
+                gh.assert_rows_match(dg, whole_g, "long rows, whole: gbest")
+                gh.assert_rows_match(dp, whole[2], "long rows, whole: pbest")
+                gh.assert_rows_match(dx, whole[0], "long rows, whole: x", close=True)
+                gh.assert_rows_match(dv, whole[1], "long rows, whole: v", close=True)
+                del whole, whole_g
+                gc.collect()
+                print("[case] long rows step 0 ok on every element", flush=True)
             assert torch.equal(dg.view(torch.int32), x_old[g_dev].view(torch.int32)), "gbest != x_g"
             for i in range(K):          # row by row: keeps the temporaries at one row
                 assert torch.equal(dx[i], x_old[i] + dv[i]), f"row {i}: x' != x + v'"

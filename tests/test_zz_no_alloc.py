@@ -40,6 +40,12 @@ def test_static_entry_point_matches_the_handle_based_one():
     both_ways(wl.small_swarm(5, 4_098, seed=72, ld=4_100, steps=3), 3, seed=72)   # smaller, right after
 
 
+def test_static_entry_point_at_its_largest_swarm():
+    K = pso.PSO_PS_STATIC_MAX_K
+    print(f"[case] allocation-free entry point: K={K} (64 words of improved flags) D=302", flush=True)
+    both_ways(wl.small_swarm(K, 302, seed=73, steps=2), 2, seed=73)
+
+
 def test_static_entry_point_rejects_what_it_cannot_hold():
     print("[case] allocation-free entry point: limits", flush=True)
     t = torch.zeros(64, dtype=torch.float32, device=gh.dev())
