@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 # with: a changed kernel reports null until the counters are taken again.
 MEASURED_TRAFFIC = {
     # profiles/update_kernel_resnet50x32_hbm_traffic.md: mean of the three timed launches
-    ("resnet50x32", "04d204538cee46f9"): 16459783000.0,
+    ("resnet50x32", "fd561d77c89a6fab"): 16459705000.0,
 }
 
 # What arithmetic-free streams over the same kind of arrays reached on one MI355X
@@ -298,7 +298,8 @@ def main() -> int:
     cfg = wl.CONFIGS[args.workload]
     K, D = cfg.K, cfg.D
     dev = torch.device("cuda:0")
-    total = args.warmup + 2 * args.steps            # the timed pass and the per-kernel pass
+    total = args.warmup + 3 * args.steps            # the timed pass, the per-kernel pass and
+                                                     # the pass with an event after every stage
     offs = [int(t) for t in args.misalign.split(",")] if args.misalign else [0, 0, 0, 0]
 
     def shifted(a, off):
@@ -384,6 +385,9 @@ def main() -> int:
         torch.cuda.synchronize()
         select_ms = [m[0].elapsed_time(m[1]) for m in marks]
         update_ms = [m[1].elapsed_time(m[2]) for m in marks]
+    # -- a third pass with an event after every stage: the spread from stage to stage --------
+    _, each_ms = time_stages(stage, args.warmup + 2 * args.steps, args.steps, stream, torch)
+    each_t = summary(each_ms)
     assert bool(torch.isfinite(dx).all()), "state went non-finite"
 
     # -- optional: the same stages replayed from a HIP graph --------------------------------
@@ -420,7 +424,12 @@ def main() -> int:
     stage_roof = {
         "what": "the whole entry-point call: one event before the first and one after the last "
                 "of the timed stages, divided by their number",
-        "bytes": stage_bytes, "ms_avg": stage_t["avg"], "achieved": stage_gbs, "frac": stage_gbs / HBM_PEAK_GBS,
+        "bytes": stage_bytes, "ms_avg": stage_t["avg"],
+        "per_stage_events": {"ms_avg": each_t["avg"], "ms_median": each_t["median"],
+                             "ms_min": each_t["min"],
+                             "what": "a further pass over as many later stages with an event "
+                                     "after every stage"},
+        "achieved": stage_gbs, "frac": stage_gbs / HBM_PEAK_GBS,
         "bytes_are": "algorithmic minimum 4*D*(5K+1): x, v read and written, pbest read or "
                      "written, gbest written once; the two-kernel split moves 4*D*(5K+3)"
         if args.variant != "average" else "4*D*(2K+1)"}
