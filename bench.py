@@ -251,6 +251,10 @@ def main() -> int:
     ap.add_argument("--fused-rows", type=int, default=0,
                     help="sync, history: the single-pass kernels with this many rows in flight per "
                          "workgroup (pso_ps_set_variant) instead of the default two kernels")
+    ap.add_argument("--best-first", type=int, default=-1,
+                    help="0: the copy-based split of the stage (selection + gbest copy, then all K "
+                         "particles) instead of the default (selection + the best particle, then "
+                         "the others)")
     ap.add_argument("--chunk-origin", type=int, default=-1,
                     help="pso_ps_set_variant's chunk_origin (default: the library's)")
     ap.add_argument("--ld", type=int, default=0,
@@ -341,8 +345,10 @@ def main() -> int:
     if args.block or args.super_tiles or args.chunk_tiles or args.wgs_per_cu or args.force_generic:
         pso.pso_ps_set_launch(h, args.block, args.super_tiles, args.chunk_tiles, args.wgs_per_cu,
                               args.force_generic)
-    if args.fused_rows or args.chunk_origin >= 0:
-        pso.pso_ps_set_variant(h, args.fused_rows, max(args.chunk_origin, 0))
+    if args.fused_rows or args.chunk_origin >= 0 or args.best_first >= 0:
+        # (a chunk origin is an option of the copy-based split's update pass)
+        best_first = args.best_first != 0 and args.chunk_origin < 0
+        pso.pso_ps_set_variant(h, args.fused_rows, max(args.chunk_origin, 0), best_first)
     stream = torch.cuda.current_stream()
 
     def stage(s, st=None):
@@ -369,22 +375,24 @@ def main() -> int:
     stage_t = summary(stage_ms)
 
     # -- a second pass over as many stages, split at the kernel boundary --------------------
-    # (sync only: pso_ps_select + pso_ps_update are the two halves of pso_ps_sync, bit for
-    # bit; an event between them gives each kernel's own duration on the launch stream)
-    select_ms, update_ms = [], []
+    # (sync only: pso_ps_sync_begin + pso_ps_sync_finish are the two launches of pso_ps_sync,
+    # bit for bit; an event between them gives each kernel's own duration on the launch stream)
+    first_ms, second_ms = [], []
     split_pass = args.variant == "sync" and not args.fused_rows
     if split_pass:
         marks = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
         for k in range(args.steps):
             s = args.warmup + args.steps + k
+            a = (h, dx, dv, dp, dpl, dloss[s], dg, w_tab[s], c1, c2, cfg.seed, s, stream)
             marks[k][0].record(stream)
-            pso.pso_ps_select(h, dx, dpl, dloss[s], dg, stream)
+            pso.pso_ps_sync_begin(*a)
             marks[k][1].record(stream)
-            pso.pso_ps_update(h, dx, dv, dp, dg, w_tab[s], c1, c2, cfg.seed, s, stream)
+            pso.pso_ps_sync_finish(*a)
             marks[k][2].record(stream)
         torch.cuda.synchronize()
-        select_ms = [m[0].elapsed_time(m[1]) for m in marks]
-        update_ms = [m[1].elapsed_time(m[2]) for m in marks]
+        first_ms = [m[0].elapsed_time(m[1]) for m in marks]
+        second_ms = [m[1].elapsed_time(m[2]) for m in marks]
+
     # -- a third pass with an event after every stage: the spread from stage to stage --------
     _, each_ms = time_stages(stage, args.warmup + 2 * args.steps, args.steps, stream, torch)
     each_t = summary(each_ms)
@@ -417,7 +425,7 @@ def main() -> int:
         kernel = "mean_kernel + broadcast_kernel"
     else:
         stage_bytes = 4.0 * D * (5 * K + 1)              # the least a stage can move (see below)
-        kernel = {"sync": "update_kernel", "rows": "select_gbest_kernel + update_rows_kernel",
+        kernel = {"sync": "update_others_kernel", "rows": "select_gbest_kernel + update_rows_kernel",
                   "segments": "select_gbest_segments_kernel + update_segments_kernel",
                   "history": "select_gbest_kernel + update_kernel"}[args.variant]
     stage_gbs = stage_bytes / (stage_t["avg"] * 1e-3) / 1e9
@@ -431,7 +439,8 @@ def main() -> int:
                                      "after every stage"},
         "achieved": stage_gbs, "frac": stage_gbs / HBM_PEAK_GBS,
         "bytes_are": "algorithmic minimum 4*D*(5K+1): x, v read and written, pbest read or "
-                     "written, gbest written once; the two-kernel split moves 4*D*(5K+3)"
+                     "written, gbest written once; the two kernels move 4*D*(5K+2), one more "
+                     "pass over gbest"
         if args.variant != "average" else "4*D*(2K+1)"}
 
     # context for the fractions: torch's own device-to-device copy of one [K, D] array on
@@ -462,29 +471,38 @@ def main() -> int:
     if args.fused_rows and args.variant in ("sync", "history"):
         kernel = "select_only_kernel + fused_rows_kernel"
     if split_pass:
-        upd, sel = summary(update_ms), summary(select_ms)
-        kernel_bytes = 4.0 * D * (5 * K + 1)             # per update launch: 20 B per particle
-        achieved = kernel_bytes / (upd["avg"] * 1e-3) / 1e9   # parameter + first read of gbest
+        second, first = summary(second_ms), summary(first_ms)
+        if args.best_first == 0 or args.chunk_origin >= 0:   # the copy-based split
+            kernel, first_kernel = "update_kernel", "select_gbest_kernel"
+            kernel_bytes = 4.0 * D * (5 * K + 1)         # K rows at 20 B + the first read of gbest
+            first_bytes = 8.0 * D                        # read row g, write gbest
+        else:                                            # the default: best particle first
+            kernel, first_kernel = "update_others_kernel", "select_move_best_kernel"
+            kernel_bytes = 4.0 * D * (5 * (K - 1) + 1)   # K-1 rows at 20 B + the first read of gbest
+            first_bytes = 24.0 * D                       # row g at 20 B + the write of gbest
+        achieved = kernel_bytes / (second["avg"] * 1e-3) / 1e9
         default_shape = not (args.block or args.super_tiles or args.chunk_tiles or args.wgs_per_cu
-                             or args.force_generic or args.misalign or args.ld)
+                             or args.force_generic or args.misalign or args.ld
+                             or args.best_first >= 0 or args.chunk_origin >= 0)
         key = (cfg.name, kernel_source_hash())
         traffic = MEASURED_TRAFFIC.get(key) if default_shape else None
         roofline = {
             "bound": "hbm", "kernel": kernel, "achieved": achieved, "peak": HBM_PEAK_GBS,
             "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
             "traffic_is": "a stored rocprofv3 --pmc reading (FETCH_SIZE + WRITE_SIZE, "
-                          "profiles/update_kernel_resnet50x32_hbm_traffic.md), valid for the kernel "
-                          "source hash it was taken with; null once the kernels have changed",
+                          "profiles/update_others_kernel_resnet50x32_hbm_traffic.md), valid for the "
+                          "kernel source hash it was taken with; null once the kernels have changed",
             "kernel_source_hash": key[1],
             "algorithmic_bytes_per_launch": kernel_bytes,
-            "kernel_ms_avg": upd["avg"], "kernel_ms_median": upd["median"],
-            "kernel_ms_min": upd["min"],
-            "kernel_pass": "a second pass over the same number of stages as pso_ps_select + "
-                           "pso_ps_update with an event between the two kernels",
-            "select_kernel": {"kernel": "select_gbest_kernel", "bytes": 8.0 * D,
-                              "ms_avg": sel["avg"], "ms_median": sel["median"], "ms_min": sel["min"],
-                              "achieved": 8.0 * D / (sel["avg"] * 1e-3) / 1e9,
-                              "frac": 8.0 * D / (sel["avg"] * 1e-3) / 1e9 / HBM_PEAK_GBS},
+            "kernel_ms_avg": second["avg"], "kernel_ms_median": second["median"],
+            "kernel_ms_min": second["min"],
+            "kernel_pass": "a second pass over the same number of stages as pso_ps_sync_begin + "
+                           "pso_ps_sync_finish with an event between the two kernels",
+            "first_kernel": {"kernel": first_kernel, "bytes": first_bytes,
+                             "ms_avg": first["avg"], "ms_median": first["median"],
+                             "ms_min": first["min"],
+                             "achieved": first_bytes / (first["avg"] * 1e-3) / 1e9,
+                             "frac": first_bytes / (first["avg"] * 1e-3) / 1e9 / HBM_PEAK_GBS},
             "stage": stage_roof,
         }
     else:

@@ -90,7 +90,7 @@ int pso_ps_create(pso_ps_ctx** out, int K, int64_t D, int64_t ld,
  *   loss          device [K], in              gbest       device [D], out
  *   w, c1, c2     inertia (paper's m) and effective accelerations
  *   seed, step    select the random numbers; the same pair reproduces them
- * Equivalent to pso_ps_select followed by pso_ps_update. */
+ * Equivalent to pso_ps_sync_begin followed by pso_ps_sync_finish. */
 int pso_ps_sync(pso_ps_ctx* h, float* x, float* v, float* pbest,
                 float* pbest_loss, const float* loss, float* gbest,
                 float w, float c1, float c2, uint64_t seed, uint64_t step,
@@ -183,21 +183,27 @@ int pso_ps_schedule(int64_t t, int64_t iteration_size, int64_t epoch_size, int64
                     float m_max, float m_min, float c1, float c2,
                     int* is_stage, float* w, float* c1_eff, float* c2_eff);
 
-/* Global search and personal-best test (steps 1, 2 and the test of step 3):
- * g = argmin loss and gbest = x_g, i.e. what Algorithm 3 returns, plus
- * improved_i = loss_i < pbest_loss_i and pbest_loss_i = min(pbest_loss_i,
- * loss_i) (Algorithm 1).  g and the improved mask stay in the handle's scratch.
- *   x  device [K, ld], read        gbest  device [D], written */
-int pso_ps_select(pso_ps_ctx* h, const float* x, float* pbest_loss, const float* loss,
-                  float* gbest, void* hip_stream);
-
-/* The per-particle part (copy of step 3 and step 4) for the selection left by
- * the last pso_ps_select on this handle (same stream): pbest_i = x_i for
- * improved particles, then Eq. (6), (7) over all K*D elements.  gbest (device
- * [D], read) is the array pso_ps_select wrote. */
-int pso_ps_update(pso_ps_ctx* h, float* x, float* v, float* pbest, const float* gbest,
-                  float w, float c1, float c2, uint64_t seed, uint64_t step,
-                  void* hip_stream);
+/* pso_ps_sync in two calls, split where its two kernel launches meet, for
+ * callers that want to time or interleave the halves.  Both take exactly the
+ * arguments of pso_ps_sync and must be given the same values, on the same
+ * stream, begin first; together they are pso_ps_sync bit for bit.
+ *   pso_ps_sync_begin   steps 1 and 2 and the test of step 3 (g, gbest, the
+ *                       improved flags; they stay in the handle's scratch),
+ *                       and step 4 for the best particle itself, whose
+ *                       position before the move is what gbest receives;
+ *   pso_ps_sync_finish  pbest_loss_i = loss_i for the improved particles and
+ *                       step 4 for the other K-1 particles.
+ * (With the copy-based split of pso_ps_set_variant, begin is the selection and
+ * the copy gbest = x_g, and finish moves all K particles.)
+ * pso_ps_sync_finish without a begin before it on this handle: PSO_PS_EINVAL. */
+int pso_ps_sync_begin(pso_ps_ctx* h, float* x, float* v, float* pbest,
+                      float* pbest_loss, const float* loss, float* gbest,
+                      float w, float c1, float c2, uint64_t seed, uint64_t step,
+                      void* hip_stream);
+int pso_ps_sync_finish(pso_ps_ctx* h, float* x, float* v, float* pbest,
+                       float* pbest_loss, const float* loss, float* gbest,
+                       float w, float c1, float c2, uint64_t seed, uint64_t step,
+                       void* hip_stream);
 
 /* Read back the last selection: waits for the stream of the last call on this
  * handle, then writes g to *g_out, the improved flags, bit i of word i/64, to
@@ -226,25 +232,31 @@ int pso_ps_last_selection(pso_ps_ctx* h, int* g_out, uint64_t* improved_mask_out
 int pso_ps_set_launch(pso_ps_ctx* h, int block_threads, int super_tiles, int chunk_tiles,
                       int wgs_per_cu, int force_generic);
 
-/* Which kernels pso_ps_sync and pso_ps_sync_history use on this handle;
- * results are bitwise the same either way.
- *   fused_rows = 0  (default) selection + gbest copy, then the update pass with
- *                   one workgroup per (particle, tile), gbest re-read through
- *                   the caches;
- *   fused_rows = P  in {1, 2, 3, 4, 6, 8}: a one-wavefront selection launch, then
- *                   a single pass in which one workgroup owns a tile of columns
- *                   for all K particles, keeps its piece of gbest on chip and
- *                   has the loads of P particles in flight (block_threads 64,
- *                   128 or 256).  Moves the fewest bytes; kept for measurement,
- *                   see the kernel's comment for when it is slower.
+/* Which kernels the flat stage uses on this handle, for measurement; results
+ * are bitwise the same in every combination.
+ *   best_first != 0 (default)  pso_ps_sync, pso_ps_sync_static: the first launch
+ *                   does the selection and moves the best particle, writing
+ *                   gbest from the values it loads anyway; the second moves
+ *                   the other K-1 particles, one workgroup per (particle,
+ *                   tile), gbest re-read through the caches.
+ *   best_first = 0  the copy-based split: selection + copy gbest = x_g, then
+ *                   all K particles.  pso_ps_sync_history always uses it (a
+ *                   stage that keeps the old gbest has no best particle to
+ *                   move first), and so do the ragged and row-pointer calls.
+ *   fused_rows = P  in {1, 2, 3, 4, 6, 8} (0: off, default): a one-wavefront
+ *                   selection launch, then a single pass in which one
+ *                   workgroup owns a tile of columns for all K particles, keeps
+ *                   its piece of gbest on chip and has the loads of P
+ *                   particles in flight (block_threads 64, 128 or 256).  Moves
+ *                   the fewest bytes and is slower; see the kernel's comment.
  *   chunk_origin    where the runs of chunk_tiles consecutive tiles that an XCD
- *                   is handed start in the update pass of the flat layout:
+ *                   is handed start in the copy-based split's update pass:
  *                   0 counted from each row's first tile; 1 at absolute
  *                   multiples of the run size in memory, run j of memory going
  *                   to XCD j mod 8; 2 at absolute multiples of the run size,
  *                   the first run of every row going to XCD 0.
- * The other entry points ignore both. */
-int pso_ps_set_variant(pso_ps_ctx* h, int fused_rows, int chunk_origin);
+ * The ragged and row-pointer entry points ignore all three. */
+int pso_ps_set_variant(pso_ps_ctx* h, int fused_rows, int chunk_origin, int best_first);
 
 /* hipError_t (as int) of the last failed HIP call on this handle, 0 if none. */
 int pso_ps_last_hip_error(const pso_ps_ctx* h);

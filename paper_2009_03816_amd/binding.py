@@ -76,8 +76,8 @@ def load():
     lib.pso_ps_create.argtypes = [PP, I, I64, I64, I, ctypes.POINTER(I64), I]
     lib.pso_ps_sync.argtypes = [P, _f32p, _f32p, _f32p, _f32p, _f32p, _f32p, F, F, F, U64, U64, P]
     lib.pso_ps_sync_segments.argtypes = [P, PP, PP, PP, _f32p, _f32p, PP, F, F, F, U64, U64, P]
-    lib.pso_ps_select.argtypes = [P, _f32p, _f32p, _f32p, _f32p, P]
-    lib.pso_ps_update.argtypes = [P, _f32p, _f32p, _f32p, _f32p, F, F, F, U64, U64, P]
+    lib.pso_ps_sync_begin.argtypes = lib.pso_ps_sync.argtypes
+    lib.pso_ps_sync_finish.argtypes = lib.pso_ps_sync.argtypes
     lib.pso_ps_last_selection.argtypes = [P, ctypes.POINTER(I), ctypes.POINTER(U64), I,
                                           ctypes.POINTER(I)]
     lib.pso_ps_sync_history.argtypes = [P, _f32p, _f32p, _f32p, _f32p, _f32p, _f32p, _f32p,
@@ -95,12 +95,12 @@ def load():
     lib.pso_ps_schedule.argtypes = [I64, I64, I64, I64, F, F, F, F, ctypes.POINTER(I),
                                     ctypes.POINTER(F), ctypes.POINTER(F), ctypes.POINTER(F)]
     lib.pso_ps_set_launch.argtypes = [P, I, I, I, I, I]
-    lib.pso_ps_set_variant.argtypes = [P, I, I]
+    lib.pso_ps_set_variant.argtypes = [P, I, I, I]
     lib.pso_ps_last_hip_error.argtypes = [P]
     lib.pso_ps_destroy.argtypes = [P]
     lib.pso_ps_strerror.argtypes = [I]
-    for name in ("pso_ps_create", "pso_ps_sync", "pso_ps_sync_segments", "pso_ps_select",
-                 "pso_ps_update", "pso_ps_last_selection", "pso_ps_set_launch", "pso_ps_set_variant",
+    for name in ("pso_ps_create", "pso_ps_sync", "pso_ps_sync_segments", "pso_ps_sync_begin",
+                 "pso_ps_sync_finish", "pso_ps_last_selection", "pso_ps_set_launch", "pso_ps_set_variant",
                  "pso_ps_sync_history", "pso_ps_sync_rows", "pso_ps_average", "pso_ps_schedule",
                  "pso_ps_sync_segments_history", "pso_ps_sync_rows_history", "pso_ps_sync_static",
                  "pso_ps_last_hip_error", "pso_ps_destroy"):
@@ -168,16 +168,18 @@ def pso_ps_sync_segments(h: int, x_seg, v_seg, pbest_seg, pbest_loss, loss, gbes
     _check(rc, "pso_ps_sync_segments", h)
 
 
-def pso_ps_select(h: int, x, pbest_loss, loss, gbest, stream=None) -> None:
-    _check(load().pso_ps_select(h, _addr(x), _addr(pbest_loss), _addr(loss), _addr(gbest),
-                                _stream(stream)), "pso_ps_select", h)
+def pso_ps_sync_begin(h: int, x, v, pbest, pbest_loss, loss, gbest, w: float, c1: float, c2: float,
+                      seed: int, step: int, stream=None) -> None:
+    rc = load().pso_ps_sync_begin(h, _addr(x), _addr(v), _addr(pbest), _addr(pbest_loss),
+                                  _addr(loss), _addr(gbest), w, c1, c2, seed, step, _stream(stream))
+    _check(rc, "pso_ps_sync_begin", h)
 
 
-def pso_ps_update(h: int, x, v, pbest, gbest, w: float, c1: float, c2: float, seed: int, step: int,
-                  stream=None) -> None:
-    rc = load().pso_ps_update(h, _addr(x), _addr(v), _addr(pbest), _addr(gbest), w, c1, c2,
-                              seed, step, _stream(stream))
-    _check(rc, "pso_ps_update", h)
+def pso_ps_sync_finish(h: int, x, v, pbest, pbest_loss, loss, gbest, w: float, c1: float, c2: float,
+                       seed: int, step: int, stream=None) -> None:
+    rc = load().pso_ps_sync_finish(h, _addr(x), _addr(v), _addr(pbest), _addr(pbest_loss),
+                                   _addr(loss), _addr(gbest), w, c1, c2, seed, step, _stream(stream))
+    _check(rc, "pso_ps_sync_finish", h)
 
 
 def pso_ps_last_selection(h: int, K: int, with_replaced: bool = False):
@@ -263,8 +265,10 @@ def pso_ps_set_launch(h: int, block_threads: int = 0, super_tiles: int = 0, chun
                                     int(force_generic)), "pso_ps_set_launch", h)
 
 
-def pso_ps_set_variant(h: int, fused_rows: int = 0, chunk_origin: int = 0) -> None:
-    _check(load().pso_ps_set_variant(h, fused_rows, chunk_origin), "pso_ps_set_variant", h)
+def pso_ps_set_variant(h: int, fused_rows: int = 0, chunk_origin: int = 0,
+                       best_first: bool = True) -> None:
+    _check(load().pso_ps_set_variant(h, fused_rows, chunk_origin, int(best_first)),
+           "pso_ps_set_variant", h)
 
 
 def pso_ps_source_hash() -> str:

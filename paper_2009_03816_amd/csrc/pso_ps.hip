@@ -201,7 +201,8 @@ __device__ __forceinline__ bool is_improved(const Selection* __restrict__ sel, i
 
 // One element of one row, element-wise accesses: ragged row ends and the
 // generic path.  `col` is the column inside the block.
-__device__ __forceinline__ void move_single(const RowPtrs& r, const float* __restrict__ gbest,
+template <bool BEST = false>
+__device__ __forceinline__ void move_single(const RowPtrs& r, float* __restrict__ gbest,
                                             unsigned long long d0, long long col, unsigned i,
                                             bool improved, const MoveParams& m) {
     const unsigned long long d = d0 + (unsigned long long)col;
@@ -210,8 +211,10 @@ __device__ __forceinline__ void move_single(const RowPtrs& r, const float* __res
     float vv = r.v[col];
     const float pv = improved ? xv : r.pbest[col];
     if (improved) r.pbest[col] = xv;
+    if (BEST) gbest[col] = xv;  // this row is the best particle: gbest = its position before the move
+    const float gb = BEST ? xv : gbest[col];
     const bool odd = d & 1ull;
-    move_element(xv, vv, pv, gbest[col], odd ? words.s2 : words.s0, odd ? words.s3 : words.s1, m);
+    move_element(xv, vv, pv, gb, odd ? words.s2 : words.s0, odd ? words.s3 : words.s1, m);
     r.x[col] = xv;
     r.v[col] = vv;
 }
@@ -225,8 +228,8 @@ __device__ __forceinline__ void move_single(const RowPtrs& r, const float* __res
 // otherwise they are two whole calls.  improved (uniform over the workgroup):
 // Algorithm 1 replaced this particle's personal best by its position, so pbest
 // is written instead of read.
-template <bool ODD>
-__device__ __forceinline__ void move_quad(const RowPtrs& r, const float* __restrict__ gbest,
+template <bool ODD, bool BEST = false>
+__device__ __forceinline__ void move_quad(const RowPtrs& r, float* __restrict__ gbest,
                                           unsigned long long d0, long long c, unsigned i,
                                           bool improved, const MoveParams& m) {
     float* xp = r.x + c;
@@ -236,8 +239,9 @@ __device__ __forceinline__ void move_quad(const RowPtrs& r, const float* __restr
     f32x4 v_old = __builtin_nontemporal_load(reinterpret_cast<const f32x4_a4*>(vp));
     f32x4 p_old = {0.0f, 0.0f, 0.0f, 0.0f};
     if (!improved) p_old = __builtin_nontemporal_load(reinterpret_cast<const f32x4_a4*>(pp));
-    f32x4 gb = *reinterpret_cast<const f32x4_a4*>(gbest + c);
-    __builtin_amdgcn_sched_barrier(0);  // all four loads are issued before anything below
+    f32x4 gb = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (!BEST) gb = *reinterpret_cast<const f32x4_a4*>(gbest + c);
+    __builtin_amdgcn_sched_barrier(0);  // all loads are issued before anything below
 
     // The random words need nothing from memory: compute them while the loads
     // are in flight.  The empty asm ties the loaded values to the last random
@@ -251,6 +255,13 @@ __device__ __forceinline__ void move_quad(const RowPtrs& r, const float* __restr
     asm volatile("" : "+v"(x_old), "+v"(v_old), "+v"(p_old), "+v"(gb)
                  : "v"(ra.s0), "v"(rb.s0), "v"(rc.s0));
 
+    if (BEST) {
+        // this row is the best particle: gbest = its position before the move
+        // (Algorithm 3), written through the caches where the other rows'
+        // pass will look for it
+        gb = x_old;
+        *reinterpret_cast<f32x4_a4*>(gbest + c) = x_old;
+    }
     const f32x4 pv = improved ? x_old : p_old;
     float xs[4] = {x_old.x, x_old.y, x_old.z, x_old.w};
     float vs[4] = {v_old.x, v_old.y, v_old.z, v_old.w};
@@ -274,8 +285,8 @@ __device__ __forceinline__ void move_quad(const RowPtrs& r, const float* __restr
 // (any 4-byte aligned row qualifies) and whole groups of four columns go
 // through move_quad; the ragged first and last columns of the row, and
 // everything without VEC (tiles then start at column 0), are element-wise.
-template <int BLOCK, bool VEC>
-__device__ __forceinline__ void update_tile(const RowPtrs& r, const float* __restrict__ gbest,
+template <int BLOCK, bool VEC, bool BEST = false>
+__device__ __forceinline__ void update_tile(const RowPtrs& r, float* __restrict__ gbest,
                                             long long n, unsigned long long d0, unsigned i,
                                             unsigned tile, bool improved, const MoveParams& m) {
     constexpr unsigned TILE = BLOCK * 4;
@@ -287,14 +298,14 @@ __device__ __forceinline__ void update_tile(const RowPtrs& r, const float* __res
         // parity of the flat index of every quad of this row (TILE and 4 are even)
         const bool odd = ((unsigned long long)phase + d0) & 1ull;
         if (odd)
-            move_quad<true>(r, gbest, d0, c, i, improved, m);
+            move_quad<true, BEST>(r, gbest, d0, c, i, improved, m);
         else
-            move_quad<false>(r, gbest, d0, c, i, improved, m);
+            move_quad<false, BEST>(r, gbest, d0, c, i, improved, m);
     } else {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const long long col = c + e;
-            if (col >= 0 && col < n) move_single(r, gbest, d0, col, i, improved, m);
+            if (col >= 0 && col < n) move_single<BEST>(r, gbest, d0, col, i, improved, m);
         }
     }
 }
@@ -349,7 +360,9 @@ __global__ __launch_bounds__(BLOCK) void update_rows_kernel(RowTable tab, const 
     if (!decode_tile_order(ord, (unsigned)rows, blockIdx.x, &i, &tile)) return;
     const RowPtrs r{tab.x[i], tab.v[i], tab.pbest[i]};
     const unsigned particle = (unsigned)row0 + i;
-    update_tile<BLOCK, VEC>(r, gbest, n, 0ull, particle, tile, is_improved(sel, (int)particle), m);
+    // (gbest is only read on this path)
+    update_tile<BLOCK, VEC>(r, const_cast<float*>(gbest), n, 0ull, particle, tile,
+                            is_improved(sel, (int)particle), m);
 }
 
 // The entry of the segment that workgroup `wg` belongs to (entries are sorted
@@ -403,7 +416,7 @@ struct TableSource {
 // Algorithm 1 against pbest_loss and stores the improved mask.
 __device__ __forceinline__ void wave_argmin(int K, const float* __restrict__ loss, float* pbest_loss,
                                             Selection* sel, bool publisher, float* best_out,
-                                            int* g_out) {
+                                            int* g_out, bool store_pbest_loss = true) {
     const int lane = threadIdx.x & 63;
     const float inf = __builtin_huge_valf();
     float best = inf;
@@ -417,7 +430,7 @@ __device__ __forceinline__ void wave_argmin(int K, const float* __restrict__ los
             if (best_i == 0x7fffffff || key < best) { best = key; best_i = i; }
             if (publisher) {
                 improved = l < pbest_loss[i];  // false if either is NaN
-                if (improved) pbest_loss[i] = l;
+                if (improved && store_pbest_loss) pbest_loss[i] = l;
             }
         }
         const unsigned long long mask = __ballot(improved);
@@ -446,11 +459,11 @@ __device__ __forceinline__ void wave_argmin(int K, const float* __restrict__ los
 __device__ __forceinline__ void select_or_recall(int K, const float* __restrict__ loss,
                                                  float* pbest_loss, Selection* sel,
                                                  const float* gbest_loss, int do_select, int* g,
-                                                 bool* replace) {
+                                                 bool* replace, bool store_pbest_loss = true) {
     if (do_select) {
         const bool publisher = blockIdx.x == 0 && threadIdx.x < 64;
         float best;
-        wave_argmin(K, loss, pbest_loss, sel, publisher, &best, g);
+        wave_argmin(K, loss, pbest_loss, sel, publisher, &best, g, store_pbest_loss);
         const float kept = gbest_loss ? *gbest_loss : 0.0f;
         *replace = gbest_loss ? (best < kept) : true;
         if (publisher && (threadIdx.x & 63) == 0) {
@@ -531,6 +544,52 @@ __global__ __launch_bounds__(kCopyBlock) void select_gbest_segments_kernel(
     unsigned row, tile;
     if (!decode_tile_order(e.ord, 1u, blockIdx.x - e.first_wg, &row, &tile)) return;
     copy_tile(e.x + (long long)g * e.n, e.gbest, e.n, tile);
+}
+
+// ---------------------------------------------------------------------------
+// The default split of the stage without history ("best first"): the first
+// launch does the selection and moves the best particle itself, writing
+// gbest = x_g from the values it has loaded anyway; the second launch moves
+// the other K-1 particles.  Against selection + copy + K-row update this reads
+// row g once less (4 D (5K+2) bytes instead of 4 D (5K+3)) and turns the copy
+// into streaming work of the update pass's kind.  pbest_loss is left alone by
+// the first launch (its workgroups need the old pbest_loss of the best
+// particle while the publisher would be overwriting it) and brought up to date
+// by workgroup 0 of the second.
+// ---------------------------------------------------------------------------
+template <int BLOCK, bool VEC>
+__global__ __launch_bounds__(BLOCK) void select_move_best_kernel(
+    ColumnBlock b, int K, const float* __restrict__ loss, float* pbest_loss, Selection* sel,
+    MoveParams m, TileOrder ord) {
+    int g;
+    bool replace;
+    select_or_recall(K, loss, pbest_loss, sel, nullptr, 1, &g, &replace, false);
+    unsigned row, tile;
+    if (!decode_tile_order(ord, 1u, blockIdx.x, &row, &tile)) return;
+    const long long off = (long long)g * b.ld;
+    const RowPtrs r{b.x + off, b.v + off, b.pbest + off};
+    const bool improved = loss[g] < pbest_loss[g];  // Algorithm 1's test, old pbest_loss
+    update_tile<BLOCK, VEC, true>(r, b.gbest, b.n, b.d0, (unsigned)g, tile, improved, m);
+}
+
+// The other K-1 particles: the grid holds K-1 rows, and row index i of it is
+// particle i, or i + 1 from the best particle on.
+template <int BLOCK, bool VEC>
+__global__ __launch_bounds__(BLOCK) void update_others_kernel(
+    ColumnBlock b, int K, const float* __restrict__ loss, float* pbest_loss,
+    const Selection* __restrict__ sel, MoveParams m, TileOrder ord) {
+    if (blockIdx.x == 0 && threadIdx.x < 64) {
+        // Algorithm 1: pbest_loss_i = loss_i for the particles that improved
+        for (int i = (int)threadIdx.x; i < K; i += 64)
+            if (is_improved(sel, i)) pbest_loss[i] = loss[i];
+    }
+    if (K < 2) return;  // the only particle is the best one
+    unsigned i, tile;
+    if (!decode_tile_order(ord, (unsigned)K - 1u, blockIdx.x, &i, &tile)) return;
+    if (i >= (unsigned)sel->g) ++i;
+    const long long row = (long long)i * b.ld;
+    const RowPtrs r{b.x + row, b.v + row, b.pbest + row};
+    update_tile<BLOCK, VEC>(r, b.gbest, b.n, b.d0, i, tile, is_improved(sel, (int)i), m);
 }
 
 // ---------------------------------------------------------------------------
@@ -775,6 +834,7 @@ struct pso_ps_ctx {
     bool force_generic;
     int fused_rows;        // 0: selection/copy kernel + update kernel; P > 0: single pass, P rows in flight
     int chunk_origin;      // 0, 1, 2: see tile_from_origin
+    bool best_first;       // flat stage without history as select_move_best_kernel + update_others_kernel
     bool eight_xcds;       // 256 compute units: the chip is driven as one device of 8 XCDs
     int last_hip_error;
 };
@@ -1047,20 +1107,84 @@ hipError_t launch_fused(const pso_ps_ctx* h, const ColumnBlock& b, const MovePar
     return hipGetLastError();
 }
 
-int enqueue_fused(pso_ps_ctx* h, const ColumnBlock& b, float* pbest_loss, const float* loss,
-                  const MoveParams& m, float* gbest_loss, hipStream_t stream) {
+int enqueue_select_only(pso_ps_ctx* h, float* pbest_loss, const float* loss, const float* gbest_loss,
+                        hipStream_t stream) {
     hipLaunchKernelGGL(select_only_kernel, dim3(1), dim3(64), 0, stream, h->K, loss, pbest_loss,
-                       h->sel, (const float*)gbest_loss);
-    hipError_t e = hipGetLastError();
+                       h->sel, gbest_loss);
+    const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(h, e);
     h->last_stream = stream;
     h->have_selection = true;
+    return PSO_PS_OK;
+}
+
+int enqueue_fused(pso_ps_ctx* h, const ColumnBlock& b, const MoveParams& m, float* gbest_loss,
+                  hipStream_t stream) {
+    hipError_t e;
     switch (block_of(h)) {
         case 64: e = launch_fused<64>(h, b, m, gbest_loss, stream); break;
         case 128: e = launch_fused<128>(h, b, m, gbest_loss, stream); break;
         case 256: e = launch_fused<256>(h, b, m, gbest_loss, stream); break;
         default: return PSO_PS_EINVAL;
     }
+    return e == hipSuccess ? PSO_PS_OK : hip_fail(h, e);
+}
+
+// The two launches of the "best first" split: see select_move_best_kernel.  The
+// first launch is short (one row), so it takes the whole compute unit (no
+// occupancy cap: 0.383 against 0.396 ms per stage at K = 8, D = 14.7 M).
+constexpr int kBestBlock = 64;
+
+int enqueue_move_best(pso_ps_ctx* h, const ColumnBlock& b, float* pbest_loss, const float* loss,
+                      const MoveParams& m, hipStream_t stream) {
+    const bool vec = vector_path(h);
+    TileOrder one;
+    unsigned long long grid = 0;
+    const unsigned long long tiles = tiles_per_row(
+        h->K, b.n, vec, kBestBlock * 4u, [&](int i) { return b.x + (long long)i * b.ld; });
+    if (!plan_order(h, 1, tiles, kBestBlock * 4u, &one, &grid))
+        return hip_fail(h, hipErrorInvalidConfiguration);
+    if (vec)
+        hipLaunchKernelGGL((select_move_best_kernel<kBestBlock, true>), dim3((unsigned)grid),
+                           dim3(kBestBlock), 0, stream, b, h->K, loss, pbest_loss, h->sel, m, one);
+    else
+        hipLaunchKernelGGL((select_move_best_kernel<kBestBlock, false>), dim3((unsigned)grid),
+                           dim3(kBestBlock), 0, stream, b, h->K, loss, pbest_loss, h->sel, m, one);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(h, e);
+    h->last_stream = stream;
+    h->have_selection = true;
+    return PSO_PS_OK;
+}
+
+template <int BLOCK>
+hipError_t launch_update_others(const pso_ps_ctx* h, const ColumnBlock& b, float* pbest_loss,
+                                const float* loss, const MoveParams& m, hipStream_t stream) {
+    const bool vec = vector_path(h);
+    const unsigned long long tiles = tiles_per_row(
+        h->K, b.n, vec, BLOCK * 4u, [&](int i) { return b.x + (long long)i * b.ld; });
+    TileOrder ord;
+    unsigned long long grid = 0;
+    // K = 1: only the pbest_loss update is left (an order for one row, unused)
+    if (!plan_order(h, h->K > 1 ? h->K - 1 : 1, tiles, BLOCK * 4u, &ord, &grid))
+        return hipErrorInvalidConfiguration;
+    if (h->K == 1) grid = 8;
+    const unsigned lds = occupancy_cap_lds(h, BLOCK);
+    if (vec)
+        hipLaunchKernelGGL((update_others_kernel<BLOCK, true>), dim3((unsigned)grid), dim3(BLOCK), lds,
+                           stream, b, h->K, loss, pbest_loss, (const Selection*)h->sel, m, ord);
+    else
+        hipLaunchKernelGGL((update_others_kernel<BLOCK, false>), dim3((unsigned)grid), dim3(BLOCK), lds,
+                           stream, b, h->K, loss, pbest_loss, (const Selection*)h->sel, m, ord);
+    return hipGetLastError();
+}
+
+int enqueue_update_others(pso_ps_ctx* h, const ColumnBlock& b, float* pbest_loss, const float* loss,
+                          const MoveParams& m, hipStream_t stream) {
+    hipError_t e;
+#define CALL(B) launch_update_others<B>(h, b, pbest_loss, loss, m, stream)
+    PSO_PS_DISPATCH_BLOCK(h, e, CALL)
+#undef CALL
     return e == hipSuccess ? PSO_PS_OK : hip_fail(h, e);
 }
 
@@ -1074,10 +1198,19 @@ MoveParams make_params(float w, float c1, float c2, uint64_t seed, uint64_t step
 
 bool is_pow2(int t) { return t > 0 && (t & (t - 1)) == 0; }
 
-// Whole flat stage; gbest_loss == null: best of this stage, else historical gBest.
+// The flat stage, or one of its two launches (parts & 1: the first, parts & 2:
+// the second); gbest_loss == null: best of this stage, else historical gBest.
+// Which kernels the two launches are:
+//   default, no history   selection + move of the best particle | the other particles
+//   history, or the copy-based split on request
+//                         selection + gbest copy | all K particles
+//   single pass on request
+//                         selection (one wavefront) | all K particles, one workgroup per column tile
 int sync_flat(pso_ps_ctx* h, float* x, float* v, float* pbest, float* pbest_loss, const float* loss,
-              float* gbest, float* gbest_loss, const MoveParams& m, hipStream_t stream) {
+              float* gbest, float* gbest_loss, const MoveParams& m, hipStream_t stream,
+              int parts = 3) {
     if (!h || !pbest_loss || !loss) return PSO_PS_EINVAL;
+    if (parts == 2 && !h->have_selection) return PSO_PS_EINVAL;
     if (!aligned_to(pbest_loss, 4) || !aligned_to(loss, 4) || !aligned_to(gbest_loss, 4))
         return PSO_PS_EALIGN;
     ColumnBlock b{x, v, pbest, gbest, (long long)h->ld, (long long)h->D, 0ull};
@@ -1085,12 +1218,29 @@ int sync_flat(pso_ps_ctx* h, float* x, float* v, float* pbest, float* pbest_loss
     if (rc != PSO_PS_OK) return rc;
     DeviceScope scope(h->device);
     if (scope.err != hipSuccess) return hip_fail(h, scope.err);
-    if (h->fused_rows > 0) return enqueue_fused(h, b, pbest_loss, loss, m, gbest_loss, stream);
-    rc = enqueue_select_gbest(h, pbest_loss, loss, StackedSource{x, b.ld}, h->K,
-                              [&](int i) { return x + (long long)i * b.ld; }, gbest, b.n,
-                              gbest_loss, true, stream);
-    if (rc != PSO_PS_OK) return rc;
-    return enqueue_update(h, b, m, gbest_loss, stream);
+    const bool fused = h->fused_rows > 0;
+    const bool best_first = !fused && h->best_first && !gbest_loss;
+    if (parts & 1) {
+        if (fused)
+            rc = enqueue_select_only(h, pbest_loss, loss, gbest_loss, stream);
+        else if (best_first)
+            rc = enqueue_move_best(h, b, pbest_loss, loss, m, stream);
+        else
+            rc = enqueue_select_gbest(h, pbest_loss, loss, StackedSource{x, b.ld}, h->K,
+                                      [&](int i) { return x + (long long)i * b.ld; }, gbest, b.n,
+                                      gbest_loss, true, stream);
+        if (rc != PSO_PS_OK) return rc;
+    }
+    if (parts & 2) {
+        if (fused)
+            rc = enqueue_fused(h, b, m, gbest_loss, stream);
+        else if (best_first)
+            rc = enqueue_update_others(h, b, pbest_loss, loss, m, stream);
+        else
+            rc = enqueue_update(h, b, m, gbest_loss, stream);
+        if (rc == PSO_PS_OK) h->last_stream = stream;
+    }
+    return rc;
 }
 
 // The ragged stage; gbest_loss as in sync_flat.
@@ -1311,7 +1461,7 @@ int pso_ps_create(pso_ps_ctx** out, int K, int64_t D, int64_t ld, int n_seg,
     h->sel_bytes = sizeof(Selection) + (size_t)(h->mask_words - 1) * sizeof(uint64_t);
     h->sel = nullptr; h->last_stream = nullptr; h->have_selection = false;
     h->block_threads = 0; h->super_tiles = 0; h->chunk_tiles = 0; h->wgs_per_cu = 0;
-    h->force_generic = false; h->fused_rows = 0; h->chunk_origin = 0; h->eight_xcds = true; h->last_hip_error = 0;
+    h->force_generic = false; h->fused_rows = 0; h->chunk_origin = 0; h->best_first = true; h->eight_xcds = true; h->last_hip_error = 0;
 
     DeviceScope scope(device);
     hipError_t e = scope.err;
@@ -1331,32 +1481,18 @@ int pso_ps_create(pso_ps_ctx** out, int K, int64_t D, int64_t ld, int n_seg,
     return PSO_PS_OK;
 }
 
-int pso_ps_select(pso_ps_ctx* h, const float* x, float* pbest_loss, const float* loss,
-                  float* gbest, void* hip_stream) {
-    if (!h || !x || !pbest_loss || !loss || !gbest) return PSO_PS_EINVAL;
-    if (!aligned_to(x, 4) || !aligned_to(pbest_loss, 4) || !aligned_to(loss, 4) ||
-        !aligned_to(gbest, 4))
-        return PSO_PS_EALIGN;
-    DeviceScope scope(h->device);
-    if (scope.err != hipSuccess) return hip_fail(h, scope.err);
-    const long long ld = (long long)h->ld;
-    return enqueue_select_gbest(h, pbest_loss, loss, StackedSource{x, ld}, h->K,
-                                [&](int i) { return x + (long long)i * ld; }, gbest,
-                                (long long)h->D, nullptr, true, (hipStream_t)hip_stream);
+int pso_ps_sync_begin(pso_ps_ctx* h, float* x, float* v, float* pbest, float* pbest_loss,
+                      const float* loss, float* gbest, float w, float c1, float c2,
+                      uint64_t seed, uint64_t step, void* hip_stream) {
+    return sync_flat(h, x, v, pbest, pbest_loss, loss, gbest, nullptr,
+                     make_params(w, c1, c2, seed, step), (hipStream_t)hip_stream, 1);
 }
 
-int pso_ps_update(pso_ps_ctx* h, float* x, float* v, float* pbest, const float* gbest,
-                  float w, float c1, float c2, uint64_t seed, uint64_t step, void* hip_stream) {
-    if (!h || !h->have_selection) return PSO_PS_EINVAL;
-    ColumnBlock b{x, v, pbest, const_cast<float*>(gbest), (long long)h->ld, (long long)h->D, 0ull};
-    const int rc = check_block(b);
-    if (rc != PSO_PS_OK) return rc;
-    DeviceScope scope(h->device);
-    if (scope.err != hipSuccess) return hip_fail(h, scope.err);
-    const int rc2 = enqueue_update(h, b, make_params(w, c1, c2, seed, step), nullptr,
-                                   (hipStream_t)hip_stream);
-    if (rc2 == PSO_PS_OK) h->last_stream = (hipStream_t)hip_stream;
-    return rc2;
+int pso_ps_sync_finish(pso_ps_ctx* h, float* x, float* v, float* pbest, float* pbest_loss,
+                       const float* loss, float* gbest, float w, float c1, float c2,
+                       uint64_t seed, uint64_t step, void* hip_stream) {
+    return sync_flat(h, x, v, pbest, pbest_loss, loss, gbest, nullptr,
+                     make_params(w, c1, c2, seed, step), (hipStream_t)hip_stream, 2);
 }
 
 int pso_ps_sync(pso_ps_ctx* h, float* x, float* v, float* pbest, float* pbest_loss,
@@ -1395,7 +1531,7 @@ int pso_ps_sync_static(int device, int K, int64_t D, int64_t ld, float* x, float
     h.sel_bytes = sizeof(Selection) + (size_t)(h.mask_words - 1) * sizeof(uint64_t);
     h.last_stream = nullptr; h.have_selection = false;
     h.block_threads = 0; h.super_tiles = 0; h.chunk_tiles = 0; h.wgs_per_cu = 0;
-    h.force_generic = false; h.fused_rows = 0; h.chunk_origin = 0; h.eight_xcds = dev.eight_xcds; h.last_hip_error = 0;
+    h.force_generic = false; h.fused_rows = 0; h.chunk_origin = 0; h.best_first = true; h.eight_xcds = dev.eight_xcds; h.last_hip_error = 0;
     return sync_flat(&h, x, v, pbest, pbest_loss, loss, gbest, nullptr,
                      make_params(w, c1, c2, seed, step), (hipStream_t)hip_stream);
 }
@@ -1534,8 +1670,9 @@ int pso_ps_set_launch(pso_ps_ctx* h, int block_threads, int super_tiles, int chu
     return PSO_PS_OK;
 }
 
-int pso_ps_set_variant(pso_ps_ctx* h, int fused_rows, int chunk_origin) {
+int pso_ps_set_variant(pso_ps_ctx* h, int fused_rows, int chunk_origin, int best_first) {
     if (!h || chunk_origin < 0 || chunk_origin > 2) return PSO_PS_EINVAL;
+    h->best_first = best_first != 0;
     switch (fused_rows) {
         case 0: case 1: case 2: case 3: case 4: case 6: case 8: break;
         default: return PSO_PS_EINVAL;

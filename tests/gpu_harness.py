@@ -55,7 +55,7 @@ class Pair:
 
     def __init__(self, sw, offset=0, block_threads: int = 0, super_tiles: int = 0,
                  chunk_tiles: int = 0, wgs_per_cu: int = 0, force_generic: bool = False,
-                 fused_rows: int = 0, chunk_origin: int = 0):
+                 fused_rows: int = 0, chunk_origin: int = 0, best_first: bool = True):
         """offset: elements by which every device array is shifted inside its
         allocation, or four of them for x, v, pbest and gbest."""
         self.sw, self.K, self.D, self.ld = sw, sw.cfg.K, sw.cfg.D, sw.ld
@@ -70,8 +70,8 @@ class Pair:
         if block_threads or super_tiles or chunk_tiles or wgs_per_cu or force_generic:
             pso.pso_ps_set_launch(self.h, block_threads, super_tiles, chunk_tiles, wgs_per_cu,
                                   force_generic)
-        if fused_rows or chunk_origin:
-            pso.pso_ps_set_variant(self.h, fused_rows, chunk_origin)
+        if fused_rows or chunk_origin or not best_first:
+            pso.pso_ps_set_variant(self.h, fused_rows, chunk_origin, best_first)
 
     def close(self):
         torch.cuda.synchronize()

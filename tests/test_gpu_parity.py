@@ -120,11 +120,14 @@ def test_odd_and_empty_segments(oracle, sizes):
     (6, 4098, 4099, (2, 1, 1, 0)),           # odd stride: the parity alternates from row to row
     (9, 70_003, 70_005, (1, 2, 3, 0)),       # the same over several tiles per row
 ])
-def test_shapes_and_alignments(oracle, K, D, ld, offset):
-    print(f"[case] K={K} D={D} ld={ld} offset={offset}", flush=True)
+@pytest.mark.parametrize("best_first", [True, False])
+def test_shapes_and_alignments(oracle, K, D, ld, offset, best_first):
+    """Both splits of the stage: selection + move of the best particle, then the
+    others (the default), and selection + gbest copy, then all K."""
+    print(f"[case] K={K} D={D} ld={ld} offset={offset} best_first={best_first}", flush=True)
     sw = wl.small_swarm(K, D, seed=100 + K + D, ld=ld, steps=3)
     sw.x[:, D:] = 7.0; sw.v[:, D:] = 7.0; sw.pbest[:, D:] = 7.0     # padding must stay untouched
-    run_trajectory(oracle, sw, steps=3, offset=offset)
+    run_trajectory(oracle, sw, steps=3, offset=offset, best_first=best_first)
 
 
 @pytest.mark.parametrize("block,sup,chunk,wgs,generic", [
@@ -133,12 +136,13 @@ def test_shapes_and_alignments(oracle, K, D, ld, offset):
     (64, 2, 1, 0, False), (64, 4, 4, 0, False), (64, 8, 2, 0, False), (128, 16, 16, 0, False),
     (256, 1, 1, 0, False), (64, 32, 8, 0, True),                         # XCD-aware orders
     (128, 0, 0, 3, False), (64, 0, 0, 8, False), (1024, 8, 2, 4, False), (256, 0, 0, 100, True)])
-def test_launch_shape_does_not_change_bits(oracle, block, sup, chunk, wgs, generic):
-    print(f"[case] block={block} super={sup} chunk={chunk} wgs_per_cu={wgs} generic={generic}",
-          flush=True)
+@pytest.mark.parametrize("best_first", [True, False])
+def test_launch_shape_does_not_change_bits(oracle, block, sup, chunk, wgs, generic, best_first):
+    print(f"[case] block={block} super={sup} chunk={chunk} wgs_per_cu={wgs} generic={generic} "
+          f"best_first={best_first}", flush=True)
     sw = wl.small_swarm(9, 70_002, seed=5, steps=2)
     run_trajectory(oracle, sw, steps=2, block_threads=block, super_tiles=sup, chunk_tiles=chunk,
-                   wgs_per_cu=wgs, force_generic=generic)
+                   wgs_per_cu=wgs, force_generic=generic, best_first=best_first)
 
 
 @pytest.mark.parametrize("origin", [1, 2])
@@ -152,7 +156,7 @@ def test_chunk_origin_does_not_change_bits(oracle, origin, block, sup, chunk, of
           f"ld={ld}", flush=True)
     sw = wl.small_swarm(9, 70_002, seed=6, ld=ld, steps=2)
     run_trajectory(oracle, sw, steps=2, offset=offset, block_threads=block, super_tiles=sup,
-                   chunk_tiles=chunk, chunk_origin=origin)
+                   chunk_tiles=chunk, chunk_origin=origin, best_first=False)
 
 
 def test_ties_nan_and_inf_losses(oracle):
@@ -377,16 +381,20 @@ def test_deterministic_and_resumable(oracle):
     pso.pso_ps_destroy(ha); pso.pso_ps_destroy(hb)
 
 
-def test_select_then_update_equals_sync(oracle):
-    print("[case] select + update == sync", flush=True)
+@pytest.mark.parametrize("best_first,fused_rows", [(True, 0), (False, 0), (True, 2)])
+def test_begin_then_finish_equals_sync(oracle, best_first, fused_rows):
+    print(f"[case] begin + finish == sync (best_first={best_first}, fused_rows={fused_rows})",
+          flush=True)
     sw = wl.small_swarm(6, 9000, seed=3, steps=1)
     one = [gh.to_dev(a) for a in (sw.x, sw.v, sw.pbest, sw.pbest_loss, np.zeros(9000, F32))]
     two = [gh.to_dev(a) for a in (sw.x, sw.v, sw.pbest, sw.pbest_loss, np.zeros(9000, F32))]
     loss = gh.to_dev(sw.losses[0])
     h = pso.pso_ps_create(6, 9000)
-    pso.pso_ps_sync(h, one[0], one[1], one[2], one[3], loss, one[4], 0.7, 1.5, 1.5, 9, 4)
-    pso.pso_ps_select(h, two[0], two[3], loss, two[4])
-    pso.pso_ps_update(h, two[0], two[1], two[2], two[4], 0.7, 1.5, 1.5, 9, 4)
+    pso.pso_ps_set_variant(h, fused_rows, 0, best_first)
+    args = (0.7, 1.5, 1.5, 9, 4)
+    pso.pso_ps_sync(h, one[0], one[1], one[2], one[3], loss, one[4], *args)
+    pso.pso_ps_sync_begin(h, two[0], two[1], two[2], two[3], loss, two[4], *args)
+    pso.pso_ps_sync_finish(h, two[0], two[1], two[2], two[3], loss, two[4], *args)
     torch.cuda.synchronize()
     for ta, tb in zip(one, two):
         assert torch.equal(ta.view(torch.int32), tb.view(torch.int32))
@@ -428,8 +436,9 @@ def test_error_codes():
         with pytest.raises(pso.PsoPsError) as e:
             call(**{name: ok + 2})
         assert e.value.code == pso.PSO_PS_EALIGN, name
-    with pytest.raises(pso.PsoPsError) as e:      # update before any select
-        pso.pso_ps_update(h, ok, ok + 256, ok + 512, ok + 900, 0.5, 1.0, 1.0, 0, 0)
+    with pytest.raises(pso.PsoPsError) as e:      # second half before any first half
+        pso.pso_ps_sync_finish(h, ok, ok + 256, ok + 512, ok + 768, ok + 800, ok + 900,
+                               0.5, 1.0, 1.0, 0, 0)
     assert e.value.code == pso.PSO_PS_EINVAL
     with pytest.raises(pso.PsoPsError) as e:      # flat handle has no segment table
         pso.pso_ps_sync_segments(h, [ok], [ok], [ok], ok, ok, [ok], 0.5, 1.0, 1.0, 0, 0)

@@ -56,6 +56,35 @@ def test_history_trajectory(oracle, K, D, steps):
         pso.pso_ps_destroy(h)
 
 
+@pytest.mark.parametrize("K,D,ld,offset,block,generic", [
+    (1, 3, 3, 0, 0, False), (1, 5_000, 5_000, 0, 0, False), (2, 7, 7, 0, 0, False),
+    (5, 4_098, 4_098, 0, 128, False), (7, 4_099, 4_099, 0, 0, False),
+    (9, 70_002, 70_004, (1, 2, 3, 0), 0, False), (33, 1_500, 1_501, (2, 0, 1, 3), 256, False),
+    (70, 300, 300, 0, 0, False), (6, 9_001, 9_001, 0, 0, True),
+])
+def test_best_first_variant(oracle, K, D, ld, offset, block, generic):
+    """The stage split as (selection + move of the best particle, which writes
+    gbest) + (move of the other K-1 particles) gives the oracle's bits, ties and
+    NaN losses included."""
+    print(f"[case] best first K={K} D={D} ld={ld} offset={offset} block={block} generic={generic}",
+          flush=True)
+    sw = wl.small_swarm(K, D, seed=400 + K, ld=ld, steps=5)
+    sw.x[:, D:] = 7.0; sw.v[:, D:] = 7.0; sw.pbest[:, D:] = 7.0
+    losses = sw.losses.copy()
+    if K >= 5:
+        losses[2, 3] = losses[2].min()               # a tie for the best
+        losses[3, 1] = losses[:3, 1].min()           # equal to its own best so far: not improved
+        losses[4] = np.nan
+        losses[4, K - 1] = 0.001                     # the last particle is the best
+    pair = gh.Pair(sw, offset=offset, block_threads=block, force_generic=generic, best_first=True)
+    try:
+        for s in range(5):
+            g, improved = pair.step(oracle, s, loss=losses[s])
+            pair.check(g, improved, f"best first step {s}")
+    finally:
+        pair.close()
+
+
 @pytest.mark.parametrize("fused_rows,block", [(1, 0), (2, 64), (3, 128), (4, 256), (6, 0), (8, 64)])
 @pytest.mark.parametrize("K,D,ld,offset", [
     (1, 3, 3, 0), (2, 7, 7, 0), (5, 4_098, 4_098, 0), (7, 4_099, 4_099, 0),      # K below / not a multiple of P
@@ -87,7 +116,7 @@ def test_single_pass_variant(oracle, fused_rows, block, K, D, ld, offset):
     h = pso.pso_ps_create(K, D, ld)
     try:
         pso.pso_ps_set_launch(h, block, 0, 0, 0, False)
-        pso.pso_ps_set_variant(h, fused_rows)
+        pso.pso_ps_set_variant(h, fused_rows, 0, True)
         reps = []
         for s in range(3):
             pso.pso_ps_sync_history(h, dev[0], dev[1], dev[2], dev[3], gh.to_dev(losses[s]), dev[4],
