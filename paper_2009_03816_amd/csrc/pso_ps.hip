@@ -1,27 +1,33 @@
 // PSO-PS synchronization step for gfx950 (MI355X): HIP kernels and the C ABI
 // declared in include/pso_ps.h.
 //
-// Two kernels per stage:
-//   select_gbest_kernel  g = argmin loss (Algorithm 3), improved_i = loss_i <
-//                        pbest_loss_i with the pbest_loss update (Algorithm 1),
-//                        and the copy gbest = x_g (Algorithm 3's return value).
-//   update_kernel        one streaming pass over [K, D]: conditional pbest
-//                        copy, Eq. (6) velocity and Eq. (7) position update.
-// The same two steps exist for K separate row arrays (update_rows_kernel, the
-// gbest copy with a TableSource) and for ragged per-tensor segments, 32 per
-// launch (select_gbest_segments_kernel, update_segments_kernel), each also with
-// the historical gBest of Section II-C.  Parameter averaging, the
-// synchronization the method replaces, is mean_kernel + broadcast_kernel.
-// fused_rows_kernel is the stage as a single pass (one workgroup owns a tile of
-// columns for all K rows and keeps its piece of gbest on chip): the fewest
-// bytes, but slower on this chip; kept selectable for measurement.
+// Two kernels per stage.  Flat layout without history (pso_ps_sync):
+//   select_move_best_kernel  g = argmin loss (Algorithm 3), improved_i = loss_i <
+//                        pbest_loss_i (Algorithm 1), and the move of the best
+//                        particle itself (Eq. (6), (7)), which stores gbest =
+//                        x_g, Algorithm 3's return value, on its way.
+//   update_others_kernel one streaming pass over the other K-1 rows of [K, D]:
+//                        conditional pbest copy, Eq. (6) velocity and Eq. (7)
+//                        position update; also brings pbest_loss up to date.
+// With the historical gBest of Section II-C, for K separate row arrays and for
+// ragged per-tensor segments (32 per launch) the split is the copy-based one:
+//   select_gbest_kernel  selection, pbest_loss update and the copy gbest = x_g
+//                        (TableSource / select_gbest_segments_kernel variants),
+//   update_kernel        the pass over all K rows (update_rows_kernel,
+//                        update_segments_kernel).
+// Parameter averaging, the synchronization the method replaces, is
+// mean_kernel + broadcast_kernel.  fused_rows_kernel is the stage as a single
+// pass (one workgroup owns a tile of columns for all K rows and keeps its piece
+// of gbest on chip): the fewest bytes, but slower on this chip; kept selectable
+// for measurement.
 //
 // The update pass is bound by HBM traffic, not by arithmetic: per particle
 // parameter it must read x and v, write x and v, and either read pbest (not
 // improved) or write it (improved; its old value is not needed because
-// pbest - x is then exactly zero): 20 bytes.  gbest costs 12 bytes per column
-// (read x_g, write gbest, first read of gbest by the update pass); the other
-// K-1 reads of a gbest tile are served by the caches.
+// pbest - x is then exactly zero): 20 bytes.  gbest costs 8 bytes per column
+// (written by the first kernel, first read by the second; 12 in the copy-based
+// split, which reads x_g once more); the other reads of a gbest tile are served
+// by the caches.
 //
 // Mapping of the update pass: one workgroup = one wavefront = one row
 // (particle) x one tile of 256 consecutive floats, one 128-bit access per
@@ -44,8 +50,9 @@
 //   * each launch reserves LDS it never touches, which caps a compute unit at
 //     about 20 resident wavefronts of the 32 it could hold: HBM serves fewer,
 //     steadier request streams better than the full house.
-// Because gbest is copied out by the first kernel, the in-place update of row g
-// cannot race with anything.
+// Because gbest is written by the first kernel, which is also the only one that
+// touches row g (or, in the copy-based split, copies it out before the update
+// pass starts), the in-place update of row g cannot race with anything.
 //
 // Compile with -ffp-contract=off: the only fused operations are the two
 // explicit fmaf of the velocity update.
@@ -547,7 +554,7 @@ __global__ __launch_bounds__(kCopyBlock) void select_gbest_segments_kernel(
 }
 
 // ---------------------------------------------------------------------------
-// The default split of the stage without history ("best first"): the first
+// The default split of the flat stage without history ("best first"): the first
 // launch does the selection and moves the best particle itself, writing
 // gbest = x_g from the values it has loaded anyway; the second launch moves
 // the other K-1 particles.  Against selection + copy + K-row update this reads
@@ -555,7 +562,10 @@ __global__ __launch_bounds__(kCopyBlock) void select_gbest_segments_kernel(
 // into streaming work of the update pass's kind.  pbest_loss is left alone by
 // the first launch (its workgroups need the old pbest_loss of the best
 // particle while the publisher would be overwriting it) and brought up to date
-// by workgroup 0 of the second.
+// by workgroup 0 of the second.  (The same split was built for the ragged and
+// the row-pointer layouts and measured no faster there - 2.56 against 2.51-2.55
+// ms with 32 separate rows, 2.56 against 2.56 with 161 tensors - so those keep
+// the copy-based split.)
 // ---------------------------------------------------------------------------
 template <int BLOCK, bool VEC>
 __global__ __launch_bounds__(BLOCK) void select_move_best_kernel(

@@ -98,6 +98,7 @@ def test_odd_and_empty_segments(oracle, sizes):
             gh.assert_bits_equal(cat(dg), hg, f"odd segments step {s}: gbest")
             gh.assert_close(cat(dx), hx, f"odd segments step {s}: x")
             gh.assert_close(cat(dv), hv, f"odd segments step {s}: v")
+            gh.assert_bits_equal(dpl.cpu().numpy(), hpl, f"odd segments step {s}: pbest_loss")
     finally:
         torch.cuda.synchronize()
         pso.pso_ps_destroy(h)
