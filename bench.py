@@ -30,16 +30,17 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 # size), keyed by workload and by the hash of the kernel source they were taken
 # with: a changed kernel reports null until the counters are taken again.
 MEASURED_TRAFFIC = {
-    # profiles/update_kernel_resnet50x32_hbm_traffic.md: mean of the three timed launches
-    ("resnet50x32", "fd561d77c89a6fab"): 16459705000.0,
+    # profiles/update_others_kernel_resnet50x32_hbm_traffic.md: update_others_kernel, mean of the
+    # three timed launches
+    ("resnet50x32", "339a0cf00ef22633"): 15948732000.0,
 }
 
 # What arithmetic-free streams over the same kind of arrays reached on one MI355X
-# (profiles/ceilings_and_rejected_variants_resnet50x32.md, a box of the slower kind): the
+# (profiles/ceilings_and_rejected_variants_resnet50x32.md, the best of each mix): the
 # practical ceilings under the 8 TB/s peak.  Stored figures of another run; the in-place
 # stream is also measured live on this run's own arrays (roofline.stream_ceiling.same_box).
 STREAM_CEILING = {
-    "in_place_3_reads_2_writes_GBps": 6380.0, "read_only_GBps": 7400.0, "copy_1r1w_GBps": 6590.0,
+    "in_place_3_reads_2_writes_GBps": 6400.0, "read_only_GBps": 7360.0, "copy_1r1w_GBps": 6630.0,
     "source": "profiles/ceilings_and_rejected_variants_resnet50x32.md (stored figures, another run)"}
 
 
