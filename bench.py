@@ -256,6 +256,9 @@ def main() -> int:
                     help="0: the copy-based split of the stage (selection + gbest copy, then all K "
                          "particles) instead of the default (selection + the best particle, then "
                          "the others)")
+    ap.add_argument("--single-launch", type=int, default=-1,
+                    help="pso_ps_set_single_launch: 1 the whole stage as one launch (K <= 64), 0 "
+                         "never, -1 (default) the library's choice: small swarms only")
     ap.add_argument("--chunk-origin", type=int, default=-1,
                     help="pso_ps_set_variant's chunk_origin (default: the library's)")
     ap.add_argument("--ld", type=int, default=0,
@@ -350,6 +353,8 @@ def main() -> int:
         # (a chunk origin is an option of the copy-based split's update pass)
         best_first = args.best_first != 0 and args.chunk_origin < 0
         pso.pso_ps_set_variant(h, args.fused_rows, max(args.chunk_origin, 0), best_first)
+    if args.single_launch >= 0:
+        pso.pso_ps_set_single_launch(h, args.single_launch)
     stream = torch.cuda.current_stream()
 
     def stage(s, st=None):
@@ -402,7 +407,7 @@ def main() -> int:
     # -- optional: the same stages replayed from a HIP graph --------------------------------
     graph_ms = None
     if args.graph:
-        per_graph = min(args.steps, 10)
+        per_graph = min(args.steps, 100)
         side = torch.cuda.Stream()
         side.wait_stream(stream)
         graph = torch.cuda.CUDAGraph()
@@ -430,7 +435,13 @@ def main() -> int:
                   "segments": "select_gbest_segments_kernel + update_segments_kernel",
                   "history": "select_gbest_kernel + update_kernel"}[args.variant]
     stage_gbs = stage_bytes / (stage_t["avg"] * 1e-3) / 1e9
+    one_launch = args.variant in ("sync", "history") and not args.fused_rows and (
+        args.single_launch == 1 or (args.single_launch < 0 and K <= 16
+                                    and K * D <= pso.PSO_PS_SINGLE_LAUNCH_MAX_PARAMS))
     stage_roof = {
+        "launches": "one: whole_stage_kernel (the per-kernel pass below is the same stage taken "
+                    "in two launches through pso_ps_sync_begin / pso_ps_sync_finish)"
+        if one_launch else "two or more: see roofline.kernel",
         "what": "the whole entry-point call: one event before the first and one after the last "
                 "of the timed stages, divided by their number",
         "bytes": stage_bytes, "ms_avg": stage_t["avg"],

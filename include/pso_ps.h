@@ -69,9 +69,14 @@ extern "C" {
 #define PSO_PS_EALIGN  (-2)  /* an array is not 4-byte aligned */
 #define PSO_PS_EHIP    (-3)  /* a HIP runtime call failed; see pso_ps_last_hip_error */
 #define PSO_PS_ENOMEM  (-4)  /* host allocation failed */
-#define PSO_PS_ELIMIT  (-5)  /* pso_ps_sync_static: K beyond PSO_PS_STATIC_MAX_K */
+#define PSO_PS_ELIMIT  (-5)  /* K beyond PSO_PS_STATIC_MAX_K (pso_ps_sync_static) or
+                                beyond PSO_PS_SINGLE_LAUNCH_MAX_K (pso_ps_set_single_launch) */
 
 #define PSO_PS_STATIC_MAX_K 4096  /* largest swarm pso_ps_sync_static accepts */
+#define PSO_PS_SINGLE_LAUNCH_MAX_K 64  /* largest swarm the single-launch stage takes */
+/* K * D up to which pso_ps_sync and pso_ps_sync_history choose the
+ * single-launch stage by themselves (for K <= 16) */
+#define PSO_PS_SINGLE_LAUNCH_MAX_PARAMS 750000
 
 typedef struct pso_ps_ctx pso_ps_ctx;
 
@@ -146,8 +151,10 @@ int pso_ps_sync_rows_history(pso_ps_ctx* h, float* const* x_rows, float* const* 
 /* pso_ps_sync for callers that cannot allocate device memory: code under HIP
  * graph capture, tight serving loops, harnesses that forbid hipMalloc.  No
  * handle: the few bytes of selection scratch that pso_ps_create would allocate
- * live in a fixed device array inside the library (about 768 bytes, held by
- * every GPU the library runs on until the process ends), so this call and
+ * live in a fixed device array inside the library (about 5 KiB: the selection
+ * record for up to PSO_PS_STATIC_MAX_K particles and the ticket counters of
+ * the single-launch stage; held by every GPU the library runs on until the
+ * process ends), so this call and
  * everything under it allocate and free nothing, on the host or the device.
  *   device        HIP device (0 .. 63) that holds the arrays
  *   K, D, ld      as for pso_ps_create; K <= PSO_PS_STATIC_MAX_K, else
@@ -156,7 +163,9 @@ int pso_ps_sync_rows_history(pso_ps_ctx* h, float* const* x_rows, float* const* 
  * All calls on one GPU share that GPU's array: calls whose work overlaps on
  * one GPU (two streams, two threads) race on it and must be serialized by the
  * caller; back-to-back calls on one stream are fine.  The array keeps the last
- * call's contents; every call rewrites all of it that it reads. */
+ * call's contents; every call rewrites all of it that it reads, and leaves the
+ * ticket counters at zero, as it found them.  The stage takes one launch or
+ * two as pso_ps_sync does by default (see pso_ps_set_single_launch). */
 int pso_ps_sync_static(int device, int K, int64_t D, int64_t ld, float* x, float* v,
                        float* pbest, float* pbest_loss, const float* loss, float* gbest,
                        float w, float c1, float c2, uint64_t seed, uint64_t step,
@@ -257,6 +266,23 @@ int pso_ps_set_launch(pso_ps_ctx* h, int block_threads, int super_tiles, int chu
  *                   the first run of every row going to XCD 0.
  * The ragged and row-pointer entry points ignore all three. */
 int pso_ps_set_variant(pso_ps_ctx* h, int fused_rows, int chunk_origin, int best_first);
+
+/* Whether pso_ps_sync and pso_ps_sync_history run the stage (Algorithm 3,
+ * Algorithm 1's pBest update, Eq. (6), (7)) as ONE kernel launch: a workgroup
+ * owns 256 columns of all K particles, one wavefront per particle; the
+ * workgroup that finishes its reads of the losses last (found by ticket
+ * counters in the handle's scratch) updates pbest_loss.  A stage of a small
+ * swarm is bound by its two dependent launches; a large one is faster in two
+ * launches, whose access order suits HBM.  Results are bitwise the same.
+ *   mode -1 (default)  single launch where it measured faster: K <= 16 (one
+ *                      wavefront per particle) and K * D <=
+ *                      PSO_PS_SINGLE_LAUNCH_MAX_PARAMS
+ *   mode 0             never
+ *   mode 1             always; PSO_PS_ELIMIT if K > PSO_PS_SINGLE_LAUNCH_MAX_K
+ * pso_ps_sync_begin / pso_ps_sync_finish, the single-pass variant of
+ * pso_ps_set_variant and the ragged and row-pointer calls always take two
+ * launches (or more); pso_ps_sync_static follows the default. */
+int pso_ps_set_single_launch(pso_ps_ctx* h, int mode);
 
 /* hipError_t (as int) of the last failed HIP call on this handle, 0 if none. */
 int pso_ps_last_hip_error(const pso_ps_ctx* h);

@@ -18,6 +18,8 @@ PSO_PS_EHIP = -3
 PSO_PS_ENOMEM = -4
 PSO_PS_ELIMIT = -5
 PSO_PS_STATIC_MAX_K = 4096
+PSO_PS_SINGLE_LAUNCH_MAX_K = 64
+PSO_PS_SINGLE_LAUNCH_MAX_PARAMS = 750_000
 
 _f32p = ctypes.c_void_p   # device addresses travel as plain pointers
 _lib = None
@@ -96,11 +98,13 @@ def load():
                                     ctypes.POINTER(F), ctypes.POINTER(F), ctypes.POINTER(F)]
     lib.pso_ps_set_launch.argtypes = [P, I, I, I, I, I]
     lib.pso_ps_set_variant.argtypes = [P, I, I, I]
+    lib.pso_ps_set_single_launch.argtypes = [P, I]
     lib.pso_ps_last_hip_error.argtypes = [P]
     lib.pso_ps_destroy.argtypes = [P]
     lib.pso_ps_strerror.argtypes = [I]
     for name in ("pso_ps_create", "pso_ps_sync", "pso_ps_sync_segments", "pso_ps_sync_begin",
                  "pso_ps_sync_finish", "pso_ps_last_selection", "pso_ps_set_launch", "pso_ps_set_variant",
+                 "pso_ps_set_single_launch",
                  "pso_ps_sync_history", "pso_ps_sync_rows", "pso_ps_average", "pso_ps_schedule",
                  "pso_ps_sync_segments_history", "pso_ps_sync_rows_history", "pso_ps_sync_static",
                  "pso_ps_last_hip_error", "pso_ps_destroy"):
@@ -269,6 +273,10 @@ def pso_ps_set_variant(h: int, fused_rows: int = 0, chunk_origin: int = 0,
                        best_first: bool = True) -> None:
     _check(load().pso_ps_set_variant(h, fused_rows, chunk_origin, int(best_first)),
            "pso_ps_set_variant", h)
+
+
+def pso_ps_set_single_launch(h: int, mode: int = -1) -> None:
+    _check(load().pso_ps_set_single_launch(h, mode), "pso_ps_set_single_launch", h)
 
 
 def pso_ps_source_hash() -> str:

@@ -623,9 +623,13 @@ __global__ __launch_bounds__(64) void select_only_kernel(int K, const float* __r
 
 // Columns c .. c+3 of a row of n columns: one 128-bit access where all four
 // exist (whole), else element by element.
+template <bool NT = true>
 __device__ __forceinline__ f32x4 load_quad(const float* __restrict__ row, long long c, long long n,
                                            bool whole) {
-    if (whole) return __builtin_nontemporal_load(reinterpret_cast<const f32x4_a4*>(row + c));
+    if (whole) {
+        if (NT) return __builtin_nontemporal_load(reinterpret_cast<const f32x4_a4*>(row + c));
+        return *reinterpret_cast<const f32x4_a4*>(row + c);
+    }
     f32x4 r = {0.0f, 0.0f, 0.0f, 0.0f};
     if (c >= 0 && c < n) r.x = row[c];
     if (c + 1 >= 0 && c + 1 < n) r.y = row[c + 1];
@@ -634,16 +638,57 @@ __device__ __forceinline__ f32x4 load_quad(const float* __restrict__ row, long l
     return r;
 }
 
+template <bool NT = true>
 __device__ __forceinline__ void store_quad(float* __restrict__ row, long long c, long long n,
                                            bool whole, f32x4 q) {
     if (whole) {
-        __builtin_nontemporal_store(q, reinterpret_cast<f32x4_a4*>(row + c));
+        if (NT) __builtin_nontemporal_store(q, reinterpret_cast<f32x4_a4*>(row + c));
+        else *reinterpret_cast<f32x4_a4*>(row + c) = q;
         return;
     }
     if (c >= 0 && c < n) row[c] = q.x;
     if (c + 1 >= 0 && c + 1 < n) row[c + 1] = q.y;
     if (c + 2 >= 0 && c + 2 < n) row[c + 2] = q.z;
     if (c + 3 >= 0 && c + 3 < n) row[c + 3] = q.w;
+}
+
+// The random words of four consecutive columns of particle i.  `pair` is the
+// random-number pair index (flat coordinate index / 2) of the first column;
+// ODD: that column is the second of its pair, so the four columns take words
+// from three Philox calls instead of two.
+struct RandomFour {
+    Words4 a, b, c;
+};
+template <bool ODD>
+__device__ __forceinline__ RandomFour draw_four(uint32_t pair, uint32_t i, const MoveParams& m) {
+    RandomFour r;
+    r.a = philox4x32_10(pair, i, m.step_lo, m.step_hi, m.key0, m.key1);
+    r.b = philox4x32_10(pair + 1u, i, m.step_lo, m.step_hi, m.key0, m.key1);
+    r.c = r.b;
+    if (ODD) r.c = philox4x32_10(pair + 2u, i, m.step_lo, m.step_hi, m.key0, m.key1);
+    return r;
+}
+
+// Eq. (6), (7) for those four columns held in registers: xq, vq are replaced
+// by the moved values.
+template <bool ODD>
+__device__ __forceinline__ void move_four(f32x4& xq, f32x4& vq, f32x4 pv, f32x4 gb,
+                                          const RandomFour& r, const MoveParams& m) {
+    float xs[4] = {xq.x, xq.y, xq.z, xq.w};
+    float vs[4] = {vq.x, vq.y, vq.z, vq.w};
+    if (!ODD) {
+        move_element(xs[0], vs[0], pv.x, gb.x, r.a.s0, r.a.s1, m);
+        move_element(xs[1], vs[1], pv.y, gb.y, r.a.s2, r.a.s3, m);
+        move_element(xs[2], vs[2], pv.z, gb.z, r.b.s0, r.b.s1, m);
+        move_element(xs[3], vs[3], pv.w, gb.w, r.b.s2, r.b.s3, m);
+    } else {
+        move_element(xs[0], vs[0], pv.x, gb.x, r.a.s2, r.a.s3, m);
+        move_element(xs[1], vs[1], pv.y, gb.y, r.b.s0, r.b.s1, m);
+        move_element(xs[2], vs[2], pv.z, gb.z, r.b.s2, r.b.s3, m);
+        move_element(xs[3], vs[3], pv.w, gb.w, r.c.s0, r.c.s1, m);
+    }
+    xq = f32x4{xs[0], xs[1], xs[2], xs[3]};
+    vq = f32x4{vs[0], vs[1], vs[2], vs[3]};
 }
 
 template <int BLOCK, int P, bool ODD>
@@ -690,28 +735,12 @@ __device__ __forceinline__ void fused_tile(const ColumnBlock& b, int K,
             const int i = base + s;
             if (i >= K) break;
             const bool improved = improved_bit(i);
-            const Words4 ra = philox4x32_10(pair, (uint32_t)i, m.step_lo, m.step_hi, m.key0, m.key1);
-            const Words4 rb = philox4x32_10(pair + 1u, (uint32_t)i, m.step_lo, m.step_hi, m.key0, m.key1);
-            Words4 rc = rb;
-            if (ODD) rc = philox4x32_10(pair + 2u, (uint32_t)i, m.step_lo, m.step_hi, m.key0, m.key1);
             const f32x4 x_old = xq[s];
-            const f32x4 pv = improved ? x_old : pq[s];
-            float xs[4] = {x_old.x, x_old.y, x_old.z, x_old.w};
-            float vs[4] = {vq[s].x, vq[s].y, vq[s].z, vq[s].w};
-            if (!ODD) {
-                move_element(xs[0], vs[0], pv.x, gb.x, ra.s0, ra.s1, m);
-                move_element(xs[1], vs[1], pv.y, gb.y, ra.s2, ra.s3, m);
-                move_element(xs[2], vs[2], pv.z, gb.z, rb.s0, rb.s1, m);
-                move_element(xs[3], vs[3], pv.w, gb.w, rb.s2, rb.s3, m);
-            } else {
-                move_element(xs[0], vs[0], pv.x, gb.x, ra.s2, ra.s3, m);
-                move_element(xs[1], vs[1], pv.y, gb.y, rb.s0, rb.s1, m);
-                move_element(xs[2], vs[2], pv.z, gb.z, rb.s2, rb.s3, m);
-                move_element(xs[3], vs[3], pv.w, gb.w, rc.s0, rc.s1, m);
-            }
+            f32x4 x_new = x_old, v_new = vq[s];
+            move_four<ODD>(x_new, v_new, improved ? x_old : pq[s], gb, draw_four<ODD>(pair, (uint32_t)i, m), m);
             const long long row = (long long)i * b.ld;
-            store_quad(b.x + row, c, b.n, whole, f32x4{xs[0], xs[1], xs[2], xs[3]});
-            store_quad(b.v + row, c, b.n, whole, f32x4{vs[0], vs[1], vs[2], vs[3]});
+            store_quad(b.x + row, c, b.n, whole, x_new);
+            store_quad(b.v + row, c, b.n, whole, v_new);
             if (improved) store_quad(b.pbest + row, c, b.n, whole, x_old);
             if (i + P < K) fetch(i + P, xq[s], vq[s], pq[s]);
         }
@@ -735,6 +764,139 @@ __global__ __launch_bounds__(BLOCK) void fused_rows_kernel(ColumnBlock b, int K,
         fused_tile<BLOCK, P, true>(b, K, sel, m, c);
     else
         fused_tile<BLOCK, P, false>(b, K, sel, m, c);
+}
+
+// ---------------------------------------------------------------------------
+// The whole stage in ONE launch, for swarms so small that a stage is bound by
+// its launches (two dependent launches cost about 4 us each) and not by
+// memory.  A workgroup owns a tile of 256 columns for all K particles and has
+// one wavefront per particle (up to kStageWaves of them; with more particles
+// a wavefront takes every W-th).  Two things in a stage are read by many and
+// overwritten in place:
+//  * x_g, which is gbest for everybody (Algorithm 3) and is moved by the
+//    wavefront that owns particle g.  Every wavefront loads its four columns
+//    of x_g before a workgroup barrier, the owner stores after it; only this
+//    workgroup touches these columns.
+//  * pbest_loss (and the historical gbest loss), which every workgroup reads
+//    for Algorithm 1's "<" test and which must end up updated.  Every
+//    workgroup takes a ticket after the barrier, i.e. after all its reads have
+//    returned; the workgroup that draws the last ticket knows that nobody will
+//    read them again and writes them, together with the selection record.
+//    Tickets are same-address atomics, which cost about 10 ns each here, so
+//    they are spread over kTicketShards counters (256 bytes apart) whose last
+//    drawers then draw from a top counter.  The last workgroup of all puts the
+//    counters back to zero for the next stage.
+// Every workgroup reaches the barrier and the ticket: no early exit.
+// ---------------------------------------------------------------------------
+constexpr int kStageWaves = 16;         // wavefronts per workgroup at most
+constexpr int kStageMaxK = PSO_PS_SINGLE_LAUNCH_MAX_K;   // one wavefront holds the whole improved mask
+static_assert(kStageMaxK <= 64, "the improved mask of the single-launch stage is one ballot");
+constexpr unsigned kStageTile = 256;    // columns per workgroup: one 128-bit group per lane
+constexpr bool kStageNT = false;         // cached accesses: these swarms live in L2 / Infinity Cache
+constexpr unsigned kTicketShards = 16;
+constexpr unsigned kTicketStride = 64;  // counters are 64 unsigned = 256 bytes apart
+constexpr size_t kTicketBytes = (size_t)(kTicketShards + 1) * kTicketStride * sizeof(unsigned);
+
+// Everything before the barrier is ordered for latency, which is all a small
+// swarm pays: the losses are requested first, then this wavefront's first
+// particle (pbest too, whether or not it turns out to be needed: waiting for
+// the "<" test would cost a round trip); the selection runs when the losses
+// are there; x_g can only be requested then; the random words are computed
+// while all of that is in flight.
+template <bool ODD>
+__device__ __forceinline__ void whole_stage_tile(const ColumnBlock& b, int K,
+                                                 const float* __restrict__ loss, float* pbest_loss,
+                                                 Selection* sel, const MoveParams& m,
+                                                 float* gbest_loss, long long c, unsigned* tickets) {
+    const int lane = (int)(threadIdx.x & 63);
+    const int w = (int)(threadIdx.x >> 6), W = (int)(blockDim.x >> 6);
+    const float inf = __builtin_huge_valf();
+    float l = inf, pl = 0.0f;
+    if (lane < K) { l = loss[lane]; pl = pbest_loss[lane]; }
+    const float kept = gbest_loss ? *gbest_loss : 0.0f;
+
+    const bool whole = c >= 0 && c + 4 <= b.n;
+    int i = w;   // W <= K: every wavefront has a first particle
+    long long row = (long long)i * b.ld;
+    f32x4 xq = load_quad<kStageNT>(b.x + row, c, b.n, whole);
+    f32x4 vq = load_quad<kStageNT>(b.v + row, c, b.n, whole);
+    f32x4 pq = load_quad<kStageNT>(b.pbest + row, c, b.n, whole);
+
+    // Algorithm 3: first argmin with NaN read as +inf (every lane gets the
+    // result); Algorithm 1: the strict "<" test, false if either side is NaN
+    float best = (l != l) ? inf : l;
+    int g = lane < K ? lane : 0x7fffffff;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const float other = __shfl_xor(best, off, 64);
+        const int other_i = __shfl_xor(g, off, 64);
+        if (other < best || (other == best && other_i < g)) { best = other; g = other_i; }
+    }
+    const unsigned long long improved_mask = __ballot(lane < K && l < pl);
+    const bool replace = gbest_loss ? (best < kept) : true;
+
+    // gbest for these columns: x_g before anybody moves, or the kept historical gbest
+    const f32x4 gb =
+        load_quad<kStageNT>(replace ? b.x + (long long)g * b.ld : b.gbest, c, b.n, whole);
+    const long long d = (long long)b.d0 + c;   // may be negative in the first tile: see fused_tile
+    const uint32_t pair = (uint32_t)(d >> 1);
+    RandomFour r = draw_four<ODD>(pair, (uint32_t)i, m);
+    asm volatile("" : "+v"(xq), "+v"(vq), "+v"(pq) : "v"(r.a.s0), "v"(r.b.s0), "v"(r.c.s0));
+    __syncthreads();   // every load above has returned, in every wavefront
+
+    // (drawing the ticket earlier, under a barrier of its own right after the
+    // losses, measured no faster)
+    unsigned ticket = 0;
+    if (threadIdx.x == 0)
+        ticket = atomicAdd(tickets + kTicketStride * (1u + blockIdx.x % kTicketShards), 1u);
+    if (w == 0 && replace) store_quad<kStageNT>(b.gbest, c, b.n, whole, gb);
+    for (;;) {
+        const bool improved = (improved_mask >> i) & 1ull;
+        const f32x4 x_old = xq;
+        move_four<ODD>(xq, vq, improved ? x_old : pq, gb, r, m);
+        store_quad<kStageNT>(b.x + row, c, b.n, whole, xq);
+        store_quad<kStageNT>(b.v + row, c, b.n, whole, vq);
+        if (improved) store_quad<kStageNT>(b.pbest + row, c, b.n, whole, x_old);
+        i += W;
+        if (i >= K) break;
+        row = (long long)i * b.ld;
+        xq = load_quad<kStageNT>(b.x + row, c, b.n, whole);
+        vq = load_quad<kStageNT>(b.v + row, c, b.n, whole);
+        if (!((improved_mask >> i) & 1ull)) pq = load_quad<kStageNT>(b.pbest + row, c, b.n, whole);
+        r = draw_four<ODD>(pair, (uint32_t)i, m);
+    }
+
+    if (threadIdx.x != 0) return;
+    const unsigned shard = blockIdx.x % kTicketShards;
+    const unsigned in_shard = (gridDim.x - shard + kTicketShards - 1u) / kTicketShards;
+    if (ticket != in_shard - 1u) return;
+    const unsigned shards = gridDim.x < kTicketShards ? gridDim.x : kTicketShards;
+    if (atomicAdd(tickets, 1u) != shards - 1u) return;
+    // Last ticket of the last shard: every workgroup has its copy of the
+    // losses.  Algorithm 1: pbest_loss_i = loss_i for the particles that improved.
+    for (int k = 0; k < K; ++k)
+        if ((improved_mask >> k) & 1ull) pbest_loss[k] = loss[k];
+    sel->g = g;
+    sel->replaced = replace ? 1 : 0;
+    sel->gbest_loss = replace ? best : kept;
+    sel->improved[0] = improved_mask;
+    if (gbest_loss) *gbest_loss = replace ? best : kept;
+    for (unsigned q = 0; q <= kTicketShards; ++q)
+        __hip_atomic_store(tickets + kTicketStride * q, 0u, __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__global__ __launch_bounds__(64 * kStageWaves) void whole_stage_kernel(
+    ColumnBlock b, int K, const float* __restrict__ loss, float* pbest_loss, Selection* sel,
+    MoveParams m, float* gbest_loss, unsigned* tickets) {
+    // tiles are aligned to the address of row 0
+    const long long phase = (long long)((reinterpret_cast<uintptr_t>(b.x) >> 2) & (kStageTile - 1u));
+    const long long c =
+        (long long)blockIdx.x * kStageTile - phase + 4 * (long long)(threadIdx.x & 63);
+    if (((unsigned long long)phase + b.d0) & 1ull)
+        whole_stage_tile<true>(b, K, loss, pbest_loss, sel, m, gbest_loss, c, tickets);
+    else
+        whole_stage_tile<false>(b, K, loss, pbest_loss, sel, m, gbest_loss, c, tickets);
 }
 
 // Parameter averaging (Section II-B, step 5) on the stacked layout, first half:
@@ -845,6 +1007,8 @@ struct pso_ps_ctx {
     int fused_rows;        // 0: selection/copy kernel + update kernel; P > 0: single pass, P rows in flight
     int chunk_origin;      // 0, 1, 2: see tile_from_origin
     bool best_first;       // flat stage without history as select_move_best_kernel + update_others_kernel
+    int single_launch;     // whole_stage_kernel: -1 where it measured faster (small swarms), 0 never, 1 wherever it can run
+    unsigned* tickets;     // device: the ticket counters of whole_stage_kernel, zero between stages
     bool eight_xcds;       // 256 compute units: the chip is driven as one device of 8 XCDs
     int last_hip_error;
 };
@@ -854,8 +1018,11 @@ struct pso_ps_ctx {
 // own copy at its own address; host code never uses the name as an address,
 // only the pointer that hipGetSymbolAddress returns for the current device.
 constexpr int kStaticMaxK = PSO_PS_STATIC_MAX_K;
-constexpr size_t kStaticScratchBytes =
+constexpr size_t kStaticSelectionBytes =
     (sizeof(Selection) + (size_t)((kStaticMaxK + 63) / 64 - 1) * sizeof(uint64_t) + 255) / 256 * 256;
+// the selection record, then the ticket counters of whole_stage_kernel, which
+// start at zero (static storage) and are put back to zero by every stage
+constexpr size_t kStaticScratchBytes = kStaticSelectionBytes + kTicketBytes;
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace {
@@ -1198,6 +1365,35 @@ int enqueue_update_others(pso_ps_ctx* h, const ColumnBlock& b, float* pbest_loss
     return e == hipSuccess ? PSO_PS_OK : hip_fail(h, e);
 }
 
+// The stage as one launch of whole_stage_kernel.
+bool single_launch_possible(const pso_ps_ctx* h) { return h->K <= kStageMaxK && h->tickets; }
+
+// Up to this many particle parameters (K * D) the single launch measured
+// faster than two launches on MI355X.
+constexpr long long kSingleLaunchMaxParams = PSO_PS_SINGLE_LAUNCH_MAX_PARAMS;
+
+bool single_launch_chosen(const pso_ps_ctx* h) {
+    if (!single_launch_possible(h) || h->single_launch == 0 || h->fused_rows > 0) return false;
+    if (h->single_launch > 0) return true;
+    // by itself only where it measured faster: one particle per wavefront
+    return h->K <= kStageWaves && (long long)h->K * (long long)h->D <= kSingleLaunchMaxParams;
+}
+
+int enqueue_whole_stage(pso_ps_ctx* h, const ColumnBlock& b, float* pbest_loss, const float* loss,
+                        const MoveParams& m, float* gbest_loss, hipStream_t stream) {
+    const unsigned long long phase = (reinterpret_cast<uintptr_t>(b.x) >> 2) & (kStageTile - 1u);
+    const unsigned long long grid = (phase + (unsigned long long)b.n + kStageTile - 1u) / kStageTile;
+    if (grid >= (1ull << 31)) return hip_fail(h, hipErrorInvalidConfiguration);
+    const int waves = h->K < kStageWaves ? h->K : kStageWaves;
+    hipLaunchKernelGGL(whole_stage_kernel, dim3((unsigned)grid), dim3(64u * (unsigned)waves), 0, stream,
+                       b, h->K, loss, pbest_loss, h->sel, m, gbest_loss, h->tickets);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(h, e);
+    h->last_stream = stream;
+    h->have_selection = true;
+    return PSO_PS_OK;
+}
+
 MoveParams make_params(float w, float c1, float c2, uint64_t seed, uint64_t step) {
     MoveParams m;
     m.w = w; m.c1 = c1; m.c2 = c2;
@@ -1216,6 +1412,8 @@ bool is_pow2(int t) { return t > 0 && (t & (t - 1)) == 0; }
 //                         selection + gbest copy | all K particles
 //   single pass on request
 //                         selection (one wavefront) | all K particles, one workgroup per column tile
+// A small swarm (or any of K <= 64 on request) takes the whole stage as one
+// launch instead, when it is not asked for in two parts.
 int sync_flat(pso_ps_ctx* h, float* x, float* v, float* pbest, float* pbest_loss, const float* loss,
               float* gbest, float* gbest_loss, const MoveParams& m, hipStream_t stream,
               int parts = 3) {
@@ -1228,6 +1426,8 @@ int sync_flat(pso_ps_ctx* h, float* x, float* v, float* pbest, float* pbest_loss
     if (rc != PSO_PS_OK) return rc;
     DeviceScope scope(h->device);
     if (scope.err != hipSuccess) return hip_fail(h, scope.err);
+    if (parts == 3 && single_launch_chosen(h))
+        return enqueue_whole_stage(h, b, pbest_loss, loss, m, gbest_loss, stream);
     const bool fused = h->fused_rows > 0;
     const bool best_first = !fused && h->best_first && !gbest_loss;
     if (parts & 1) {
@@ -1472,6 +1672,7 @@ int pso_ps_create(pso_ps_ctx** out, int K, int64_t D, int64_t ld, int n_seg,
     h->sel = nullptr; h->last_stream = nullptr; h->have_selection = false;
     h->block_threads = 0; h->super_tiles = 0; h->chunk_tiles = 0; h->wgs_per_cu = 0;
     h->force_generic = false; h->fused_rows = 0; h->chunk_origin = 0; h->best_first = true; h->eight_xcds = true; h->last_hip_error = 0;
+    h->single_launch = -1; h->tickets = nullptr;
 
     DeviceScope scope(device);
     hipError_t e = scope.err;
@@ -1481,7 +1682,10 @@ int pso_ps_create(pso_ps_ctx** out, int K, int64_t D, int64_t ld, int n_seg,
     h->eight_xcds = compute_units == 256;
     if (e == hipSuccess) e = hipMalloc((void**)&h->sel, h->sel_bytes);
     if (e == hipSuccess) e = hipMemset(h->sel, 0, h->sel_bytes);
+    if (e == hipSuccess) e = hipMalloc((void**)&h->tickets, kTicketBytes);
+    if (e == hipSuccess) e = hipMemset(h->tickets, 0, kTicketBytes);
     if (e != hipSuccess) {
+        if (h->tickets) (void)hipFree(h->tickets);
         if (h->sel) (void)hipFree(h->sel);
         delete h;
         (void)hipGetLastError();
@@ -1542,6 +1746,9 @@ int pso_ps_sync_static(int device, int K, int64_t D, int64_t ld, float* x, float
     h.last_stream = nullptr; h.have_selection = false;
     h.block_threads = 0; h.super_tiles = 0; h.chunk_tiles = 0; h.wgs_per_cu = 0;
     h.force_generic = false; h.fused_rows = 0; h.chunk_origin = 0; h.best_first = true; h.eight_xcds = dev.eight_xcds; h.last_hip_error = 0;
+    h.single_launch = -1;
+    h.tickets = reinterpret_cast<unsigned*>(reinterpret_cast<unsigned char*>(dev.ptr) +
+                                            kStaticSelectionBytes);
     return sync_flat(&h, x, v, pbest, pbest_loss, loss, gbest, nullptr,
                      make_params(w, c1, c2, seed, step), (hipStream_t)hip_stream);
 }
@@ -1692,6 +1899,13 @@ int pso_ps_set_variant(pso_ps_ctx* h, int fused_rows, int chunk_origin, int best
     return PSO_PS_OK;
 }
 
+int pso_ps_set_single_launch(pso_ps_ctx* h, int mode) {
+    if (!h || mode < -1 || mode > 1) return PSO_PS_EINVAL;
+    if (mode == 1 && !single_launch_possible(h)) return PSO_PS_ELIMIT;
+    h->single_launch = mode;
+    return PSO_PS_OK;
+}
+
 int pso_ps_last_hip_error(const pso_ps_ctx* h) { return h ? h->last_hip_error : 0; }
 
 int pso_ps_destroy(pso_ps_ctx* h) {
@@ -1700,6 +1914,7 @@ int pso_ps_destroy(pso_ps_ctx* h) {
     {
         DeviceScope scope(h->device);
         if (h->sel && hipFree(h->sel) != hipSuccess) rc = PSO_PS_EHIP;
+        if (h->tickets && hipFree(h->tickets) != hipSuccess) rc = PSO_PS_EHIP;
     }
     delete h;
     return rc;
@@ -1721,7 +1936,9 @@ const char* pso_ps_strerror(int code) {
         case PSO_PS_EALIGN: return "array not 4-byte aligned";
         case PSO_PS_EHIP: return "HIP runtime call failed";
         case PSO_PS_ENOMEM: return "host allocation failed";
-        case PSO_PS_ELIMIT: return "size beyond the fixed scratch of the allocation-free entry point";
+        case PSO_PS_ELIMIT:
+            return "more particles than the fixed scratch of the allocation-free entry point or the "
+                   "single-launch stage holds";
         default: return "unknown status code";
     }
 }

@@ -55,9 +55,14 @@ class Pair:
 
     def __init__(self, sw, offset=0, block_threads: int = 0, super_tiles: int = 0,
                  chunk_tiles: int = 0, wgs_per_cu: int = 0, force_generic: bool = False,
-                 fused_rows: int = 0, chunk_origin: int = 0, best_first: bool = True):
+                 fused_rows: int = 0, chunk_origin: int = 0, best_first: bool = True,
+                 single_launch=None):
         """offset: elements by which every device array is shifted inside its
-        allocation, or four of them for x, v, pbest and gbest."""
+        allocation, or four of them for x, v, pbest and gbest.  The launch-shape
+        and variant switches concern the stage in two launches: a caller that
+        sets one of them gets that stage unless it says otherwise
+        (single_launch: None = the handle's default, else the mode of
+        pso_ps_set_single_launch)."""
         self.sw, self.K, self.D, self.ld = sw, sw.cfg.K, sw.cfg.D, sw.ld
         self.hx, self.hv, self.hp = sw.x.copy(), sw.v.copy(), sw.pbest.copy()
         self.hpl = sw.pbest_loss.copy()
@@ -67,11 +72,22 @@ class Pair:
         self.dpl = to_dev(sw.pbest_loss)
         self.dg = torch.zeros(self.D + offs[3], dtype=torch.float32, device=dev())[offs[3]:]
         self.h = pso.pso_ps_create(self.K, self.D, self.ld)
-        if block_threads or super_tiles or chunk_tiles or wgs_per_cu or force_generic:
-            pso.pso_ps_set_launch(self.h, block_threads, super_tiles, chunk_tiles, wgs_per_cu,
-                                  force_generic)
-        if fused_rows or chunk_origin or not best_first:
-            pso.pso_ps_set_variant(self.h, fused_rows, chunk_origin, best_first)
+        try:
+            if block_threads or super_tiles or chunk_tiles or wgs_per_cu or force_generic:
+                pso.pso_ps_set_launch(self.h, block_threads, super_tiles, chunk_tiles, wgs_per_cu,
+                                      force_generic)
+            if fused_rows or chunk_origin or not best_first:
+                pso.pso_ps_set_variant(self.h, fused_rows, chunk_origin, best_first)
+            shaped = (block_threads or super_tiles or chunk_tiles or wgs_per_cu or force_generic
+                      or fused_rows or chunk_origin or not best_first)
+            if single_launch is None and shaped:
+                single_launch = 0
+            if single_launch is not None:
+                pso.pso_ps_set_single_launch(self.h, single_launch)
+        except Exception:
+            pso.pso_ps_destroy(self.h)
+            self.h = None
+            raise
 
     def close(self):
         torch.cuda.synchronize()

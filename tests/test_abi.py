@@ -26,6 +26,15 @@ def test_library_exports_every_declared_function():
         assert hasattr(pso, name), f"binding lacks {name}"
 
 
+def test_binding_constants_are_the_headers():
+    text = open(os.path.join(ROOT, "include", "pso_ps.h")).read()
+    defines = dict(re.findall(r"^#define\s+(PSO_PS_[A-Z_]+)\s+\(?(-?\d+)\)?", text, flags=re.M))
+    assert {"PSO_PS_OK", "PSO_PS_ELIMIT", "PSO_PS_STATIC_MAX_K", "PSO_PS_SINGLE_LAUNCH_MAX_K",
+            "PSO_PS_SINGLE_LAUNCH_MAX_PARAMS"} <= set(defines)
+    for name, value in defines.items():
+        assert getattr(pso, name) == int(value), name
+
+
 def test_status_texts_and_argument_checks_without_a_gpu():
     assert pso.pso_ps_strerror(pso.PSO_PS_OK) == "ok"
     for code in (pso.PSO_PS_EINVAL, pso.PSO_PS_EALIGN, pso.PSO_PS_EHIP, pso.PSO_PS_ENOMEM, -99):

@@ -26,16 +26,16 @@ def run_trajectory(oracle, sw, steps=None, **kw):
 
 
 @pytest.mark.parametrize("name", ["mlp", "lenet5", "resnet20"])
-def test_config_trajectory(oracle, name):
-    print(f"[case] config {name}, dense rows", flush=True)
+def test_config_trajectory(oracle, name, stage_launches):
+    print(f"[case] config {name}, dense rows, {stage_launches}", flush=True)
     run_trajectory(oracle, wl.make_swarm(wl.CONFIGS[name]))
 
 
 @pytest.mark.parametrize("name", ["mlp", "resnet20"])
-def test_config_trajectory_padded_rows(oracle, name):
+def test_config_trajectory_padded_rows(oracle, name, stage_launches):
     cfg = wl.CONFIGS[name]
     ld = (cfg.D + 3) // 4 * 4 + 4
-    print(f"[case] config {name}, ld={ld}", flush=True)
+    print(f"[case] config {name}, ld={ld}, {stage_launches}", flush=True)
     run_trajectory(oracle, wl.make_swarm(cfg, ld=ld), steps=min(cfg.steps, 6))
 
 
@@ -121,14 +121,20 @@ def test_odd_and_empty_segments(oracle, sizes):
     (6, 4098, 4099, (2, 1, 1, 0)),           # odd stride: the parity alternates from row to row
     (9, 70_003, 70_005, (1, 2, 3, 0)),       # the same over several tiles per row
 ])
-@pytest.mark.parametrize("best_first", [True, False])
-def test_shapes_and_alignments(oracle, K, D, ld, offset, best_first):
-    """Both splits of the stage: selection + move of the best particle, then the
-    others (the default), and selection + gbest copy, then all K."""
-    print(f"[case] K={K} D={D} ld={ld} offset={offset} best_first={best_first}", flush=True)
+@pytest.mark.parametrize("stage", ["best_first", "copy", "single_launch"])
+def test_shapes_and_alignments(oracle, K, D, ld, offset, stage):
+    """The three shapes of the stage: selection + move of the best particle, then
+    the others; selection + gbest copy, then all K; everything in one launch."""
+    print(f"[case] K={K} D={D} ld={ld} offset={offset} stage={stage}", flush=True)
     sw = wl.small_swarm(K, D, seed=100 + K + D, ld=ld, steps=3)
     sw.x[:, D:] = 7.0; sw.v[:, D:] = 7.0; sw.pbest[:, D:] = 7.0     # padding must stay untouched
-    run_trajectory(oracle, sw, steps=3, offset=offset, best_first=best_first)
+    if stage == "single_launch" and K > pso.PSO_PS_SINGLE_LAUNCH_MAX_K:
+        with pytest.raises(pso.PsoPsError) as err:
+            gh.Pair(sw, offset=offset, single_launch=1)
+        assert err.value.code == pso.PSO_PS_ELIMIT
+        return
+    run_trajectory(oracle, sw, steps=3, offset=offset, best_first=stage != "copy",
+                   single_launch=1 if stage == "single_launch" else 0)
 
 
 @pytest.mark.parametrize("block,sup,chunk,wgs,generic", [
@@ -160,7 +166,7 @@ def test_chunk_origin_does_not_change_bits(oracle, origin, block, sup, chunk, of
                    chunk_tiles=chunk, chunk_origin=origin, best_first=False)
 
 
-def test_ties_nan_and_inf_losses(oracle):
+def test_ties_nan_and_inf_losses(oracle, stage_launches):
     K, D = 8, 5000
     print(f"[case] ties / NaN / inf losses K={K} D={D}", flush=True)
     sw = wl.small_swarm(K, D, seed=77, steps=1)
@@ -180,7 +186,7 @@ def test_ties_nan_and_inf_losses(oracle):
         pair.close()
 
 
-def test_random_shapes_alignments_and_layouts(oracle):
+def test_random_shapes_alignments_and_layouts(oracle, stage_launches):
     """Sixty seeded random cases: K, D, row stride, buffer offsets (which pick
     the 128-bit or the element-wise path and shift the tile phase), launch shape,
     and for every third case a ragged split of the columns."""
@@ -224,7 +230,9 @@ def test_random_shapes_alignments_and_layouts(oracle):
                 torch.cuda.synchronize()
                 pso.pso_ps_destroy(h)
         else:
-            pair = gh.Pair(sw, offset=offset, block_threads=block, super_tiles=sup, chunk_tiles=chunk)
+            single = stage_launches == "single_launch" and K <= pso.PSO_PS_SINGLE_LAUNCH_MAX_K
+            pair = gh.Pair(sw, offset=offset, block_threads=block, super_tiles=sup, chunk_tiles=chunk,
+                           single_launch=1 if single else 0)
             try:
                 for s in range(2):
                     g, improved = pair.step(oracle, s, seed=seed)
@@ -233,7 +241,7 @@ def test_random_shapes_alignments_and_layouts(oracle):
                 pair.close()
 
 
-def test_seed_and_step_use_all_64_bits(oracle):
+def test_seed_and_step_use_all_64_bits(oracle, stage_launches):
     print("[case] 64-bit seed and step", flush=True)
     K, D = 3, 4100
     sw = wl.small_swarm(K, D, seed=19, steps=1)
@@ -258,7 +266,7 @@ def test_seed_and_step_use_all_64_bits(oracle):
             assert not np.array_equal(results[a], results[b])   # the high halves matter
 
 
-def test_subnormal_values_are_kept(oracle):
+def test_subnormal_values_are_kept(oracle, stage_launches):
     """Positions and velocities in the subnormal range: both sides keep
     gradual underflow, so the bits still agree."""
     print("[case] subnormal inputs", flush=True)
@@ -267,7 +275,7 @@ def test_subnormal_values_are_kept(oracle):
     run_trajectory(oracle, sw, steps=3)
 
 
-def test_non_finite_positions_propagate(oracle):
+def test_non_finite_positions_propagate(oracle, stage_launches):
     """inf and NaN in x, v: the same elements become NaN/inf on both sides
     (the bit pattern of a NaN is not part of the contract), the rest agrees in bits."""
     print("[case] non-finite positions", flush=True)
@@ -290,7 +298,7 @@ def test_non_finite_positions_propagate(oracle):
         pair.close()
 
 
-def test_two_handles_on_two_streams(oracle):
+def test_two_handles_on_two_streams(oracle, stage_launches):
     """Independent swarms on their own handles and streams do not disturb each other."""
     print("[case] two handles, two streams", flush=True)
     a, b = wl.small_swarm(5, 30_000, seed=13, steps=4), wl.small_swarm(7, 20_002, seed=14, steps=4)
@@ -314,7 +322,7 @@ def test_two_handles_on_two_streams(oracle):
         pa.close(); pb.close()
 
 
-def test_stage_can_be_captured_in_a_hip_graph(oracle):
+def test_stage_can_be_captured_in_a_hip_graph(oracle, stage_launches):
     """A stage allocates nothing, copies nothing to the host and clears no
     memory, so it can be recorded into a HIP graph; every replay (with eager
     work and synchronisation in between) gives the bits of the eager call."""
@@ -356,7 +364,7 @@ def test_stage_can_be_captured_in_a_hip_graph(oracle):
         pso.pso_ps_destroy(he); pso.pso_ps_destroy(hg)
 
 
-def test_deterministic_and_resumable(oracle):
+def test_deterministic_and_resumable(oracle, stage_launches):
     """Same (seed, step) gives the same bits; five stages, a new handle and
     five more equal ten stages in one go."""
     print("[case] determinism / resume", flush=True)
@@ -382,16 +390,20 @@ def test_deterministic_and_resumable(oracle):
     pso.pso_ps_destroy(ha); pso.pso_ps_destroy(hb)
 
 
-@pytest.mark.parametrize("best_first,fused_rows", [(True, 0), (False, 0), (True, 2)])
-def test_begin_then_finish_equals_sync(oracle, best_first, fused_rows):
-    print(f"[case] begin + finish == sync (best_first={best_first}, fused_rows={fused_rows})",
-          flush=True)
+@pytest.mark.parametrize("best_first,fused_rows,single", [(True, 0, 0), (False, 0, 0), (True, 2, 0),
+                                                          (True, 0, 1), (False, 0, 1)])
+def test_begin_then_finish_equals_sync(oracle, best_first, fused_rows, single):
+    """pso_ps_sync_begin + pso_ps_sync_finish are the stage in two launches;
+    pso_ps_sync is the same two launches (single = 0) or the whole stage in one."""
+    print(f"[case] begin + finish == sync (best_first={best_first}, fused_rows={fused_rows}, "
+          f"single_launch={single})", flush=True)
     sw = wl.small_swarm(6, 9000, seed=3, steps=1)
     one = [gh.to_dev(a) for a in (sw.x, sw.v, sw.pbest, sw.pbest_loss, np.zeros(9000, F32))]
     two = [gh.to_dev(a) for a in (sw.x, sw.v, sw.pbest, sw.pbest_loss, np.zeros(9000, F32))]
     loss = gh.to_dev(sw.losses[0])
     h = pso.pso_ps_create(6, 9000)
     pso.pso_ps_set_variant(h, fused_rows, 0, best_first)
+    pso.pso_ps_set_single_launch(h, single)
     args = (0.7, 1.5, 1.5, 9, 4)
     pso.pso_ps_sync(h, one[0], one[1], one[2], one[3], loss, one[4], *args)
     pso.pso_ps_sync_begin(h, two[0], two[1], two[2], two[3], loss, two[4], *args)
@@ -402,7 +414,22 @@ def test_begin_then_finish_equals_sync(oracle, best_first, fused_rows):
     pso.pso_ps_destroy(h)
 
 
-def test_runs_on_a_side_stream(oracle):
+def test_launch_shape_can_change_between_stages(oracle):
+    """One launch, two launches, one again, ...: the ticket counters of the
+    single launch are back at zero after every stage that used them."""
+    print("[case] single launch and two launches alternating on one handle", flush=True)
+    sw = wl.small_swarm(7, 12_345, seed=31, steps=6)
+    pair = gh.Pair(sw)
+    try:
+        for s in range(6):
+            pso.pso_ps_set_single_launch(pair.h, (1, 0, 1, 1, 0, -1)[s])
+            g, improved = pair.step(oracle, s)
+            pair.check(g, improved, f"alternating step {s}")
+    finally:
+        pair.close()
+
+
+def test_runs_on_a_side_stream(oracle, stage_launches):
     print("[case] non-default stream", flush=True)
     sw = wl.small_swarm(4, 4096, seed=12, steps=1)
     side = torch.cuda.Stream()
@@ -447,6 +474,16 @@ def test_error_codes():
     for bad in [(100, 0, 0), (256, 3, 0), (256, 0, 6), (256, 0, 0, 2), (256, 0, 0, -1)]:
         with pytest.raises(pso.PsoPsError):
             pso.pso_ps_set_launch(h, *bad)
+    for bad in (-2, 2):
+        with pytest.raises(pso.PsoPsError) as e:
+            pso.pso_ps_set_single_launch(h, bad)
+        assert e.value.code == pso.PSO_PS_EINVAL
+    big = pso.pso_ps_create(pso.PSO_PS_SINGLE_LAUNCH_MAX_K + 1, 10)
+    with pytest.raises(pso.PsoPsError) as e:      # more particles than the single launch takes
+        pso.pso_ps_set_single_launch(big, 1)
+    assert e.value.code == pso.PSO_PS_ELIMIT
+    pso.pso_ps_set_single_launch(big, -1)         # the default is always accepted
+    pso.pso_ps_destroy(big)
     torch.cuda.synchronize()
     assert not t.any()                           # nothing was enqueued by the failed calls
     pso.pso_ps_destroy(h)

@@ -24,7 +24,7 @@ def compare_state(dev, host, what):
 
 
 @pytest.mark.parametrize("K,D,steps", [(6, 10_242, 14), (8, 1_000_002, 6)])
-def test_history_trajectory(oracle, K, D, steps):
+def test_history_trajectory(oracle, K, D, steps, stage_launches):
     print(f"[case] historical gBest K={K} D={D}", flush=True)
     sw = wl.small_swarm(K, D, seed=31, steps=steps)
     losses = sw.losses.copy()
@@ -265,7 +265,7 @@ def test_parameter_averaging(oracle, K, D, ld, offset):
         pso.pso_ps_destroy(h)
 
 
-def test_run_with_the_papers_schedule(oracle):
+def test_run_with_the_papers_schedule(oracle, stage_launches):
     """Table II constants, inertia by Eq. (5), lambda = epoch number, a stage
     every 10th iteration: the library's schedule drives the library, the
     oracle's schedule drives the oracle."""
