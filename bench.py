@@ -357,6 +357,12 @@ def main() -> int:
         pso.pso_ps_set_single_launch(h, args.single_launch)
     stream = torch.cuda.current_stream()
 
+    # host arrays of device pointers for the ragged and row-pointer calls, built once
+    if args.variant == "rows":
+        xr_t, vr_t, pr_t = (pso.pso_ps_pointer_table(t) for t in (xr, vr, pr))
+    elif args.variant == "segments":
+        xs_t, vs_t, ps_t, gs_t = (pso.pso_ps_pointer_table(t) for t in (xs, vs, ps, gs))
+
     def stage(s, st=None):
         """One whole synchronization stage through the entry point of the variant."""
         st = st or stream
@@ -366,9 +372,10 @@ def main() -> int:
             pso.pso_ps_sync_history(h, dx, dv, dp, dpl, dloss[s], dg, dgl, w_tab[s], c1, c2,
                                     cfg.seed, s, st)
         elif args.variant == "rows":
-            pso.pso_ps_sync_rows(h, xr, vr, pr, dpl, dloss[s], dg, w_tab[s], c1, c2, cfg.seed, s, st)
+            pso.pso_ps_sync_rows(h, xr_t, vr_t, pr_t, dpl, dloss[s], dg, w_tab[s], c1, c2, cfg.seed,
+                                 s, st)
         elif args.variant == "segments":
-            pso.pso_ps_sync_segments(h, xs, vs, ps, dpl, dloss[s], gs, w_tab[s], c1, c2,
+            pso.pso_ps_sync_segments(h, xs_t, vs_t, ps_t, dpl, dloss[s], gs_t, w_tab[s], c1, c2,
                                      cfg.seed, s, st)
         else:
             pso.pso_ps_average(h, dx, dg, st)
@@ -435,7 +442,9 @@ def main() -> int:
                   "segments": "select_gbest_segments_kernel + update_segments_kernel",
                   "history": "select_gbest_kernel + update_kernel"}[args.variant]
     stage_gbs = stage_bytes / (stage_t["avg"] * 1e-3) / 1e9
-    one_launch = args.variant in ("sync", "history") and not args.fused_rows and (
+    fits_one = args.variant in ("sync", "history") or (
+        args.variant == "segments" and sum(1 for n in cfg.segments if n > 0) <= 32)
+    one_launch = fits_one and not args.fused_rows and (
         args.single_launch == 1 or (args.single_launch < 0 and K <= 16
                                     and K * D <= pso.PSO_PS_SINGLE_LAUNCH_MAX_PARAMS))
     stage_roof = {

@@ -267,9 +267,10 @@ int pso_ps_set_launch(pso_ps_ctx* h, int block_threads, int super_tiles, int chu
  * The ragged and row-pointer entry points ignore all three. */
 int pso_ps_set_variant(pso_ps_ctx* h, int fused_rows, int chunk_origin, int best_first);
 
-/* Whether pso_ps_sync and pso_ps_sync_history run the stage (Algorithm 3,
- * Algorithm 1's pBest update, Eq. (6), (7)) as ONE kernel launch: a workgroup
- * owns 256 columns of all K particles, one wavefront per particle; the
+/* Whether pso_ps_sync, pso_ps_sync_history, the ragged and the row-pointer
+ * calls run the stage (Algorithm 3, Algorithm 1's pBest update, Eq. (6), (7))
+ * as ONE kernel launch: a workgroup owns 256 columns of all K particles, one
+ * wavefront per particle (with K > 16 a wavefront takes several); the
  * workgroup that finishes its reads of the losses last (found by ticket
  * counters in the handle's scratch) updates pbest_loss.  A stage of a small
  * swarm is bound by its two dependent launches; a large one is faster in two
@@ -279,9 +280,11 @@ int pso_ps_set_variant(pso_ps_ctx* h, int fused_rows, int chunk_origin, int best
  *                      PSO_PS_SINGLE_LAUNCH_MAX_PARAMS
  *   mode 0             never
  *   mode 1             always; PSO_PS_ELIMIT if K > PSO_PS_SINGLE_LAUNCH_MAX_K
- * pso_ps_sync_begin / pso_ps_sync_finish, the single-pass variant of
- * pso_ps_set_variant and the ragged and row-pointer calls always take two
- * launches (or more); pso_ps_sync_static follows the default. */
+ * The row-pointer calls follow the same setting, and so do the ragged calls
+ * when the handle has at most 32 non-empty segments (a workgroup then owns 256
+ * columns of one segment); pso_ps_sync_static follows the default.
+ * pso_ps_sync_begin / pso_ps_sync_finish and the single-pass variant of
+ * pso_ps_set_variant always take two launches. */
 int pso_ps_set_single_launch(pso_ps_ctx* h, int mode);
 
 /* hipError_t (as int) of the last failed HIP call on this handle, 0 if none. */

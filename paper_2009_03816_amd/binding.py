@@ -133,7 +133,17 @@ def _stream(stream) -> Optional[int]:
 
 
 def _table(ptrs: Sequence):
+    if isinstance(ptrs, ctypes.Array):
+        return ptrs
     return (ctypes.c_void_p * len(ptrs))(*[_addr(p) for p in ptrs])
+
+
+def pso_ps_pointer_table(arrays: Sequence):
+    """The host array of device pointers that the ragged and row-pointer calls
+    take, built once from tensors (or raw addresses) whose memory stays where
+    it is: passing it instead of the list saves the per-call marshalling.  The
+    caller keeps the tensors alive."""
+    return _table(list(arrays))
 
 
 def _check(rc: int, where: str, h=None):

@@ -791,6 +791,7 @@ __global__ __launch_bounds__(BLOCK) void fused_rows_kernel(ColumnBlock b, int K,
 constexpr int kStageWaves = 16;         // wavefronts per workgroup at most
 constexpr int kStageMaxK = PSO_PS_SINGLE_LAUNCH_MAX_K;   // one wavefront holds the whole improved mask
 static_assert(kStageMaxK <= 64, "the improved mask of the single-launch stage is one ballot");
+static_assert(kStageMaxK <= kTableRows, "a row-pointer launch carries every particle of the single-launch stage");
 constexpr unsigned kStageTile = 256;    // columns per workgroup: one 128-bit group per lane
 constexpr bool kStageNT = false;         // cached accesses: these swarms live in L2 / Infinity Cache
 constexpr unsigned kTicketShards = 16;
@@ -803,8 +804,25 @@ constexpr size_t kTicketBytes = (size_t)(kTicketShards + 1) * kTicketStride * si
 // the "<" test would cost a round trip); the selection runs when the losses
 // are there; x_g can only be requested then; the random words are computed
 // while all of that is in flight.
-template <bool ODD>
-__device__ __forceinline__ void whole_stage_tile(const ColumnBlock& b, int K,
+// `rows` says where particle i's x, v and pbest start (stacked with a stride,
+// or K separate arrays); `b` carries gbest, the number of columns and d0.
+struct StackedRows {
+    float* x;
+    float* v;
+    float* pbest;
+    long long ld;
+    __device__ RowPtrs row(int i) const {
+        const long long off = (long long)i * ld;
+        return RowPtrs{x + off, v + off, pbest + off};
+    }
+};
+struct TableRows {
+    RowTable tab;
+    __device__ RowPtrs row(int i) const { return RowPtrs{tab.x[i], tab.v[i], tab.pbest[i]}; }
+};
+
+template <bool ODD, class Rows>
+__device__ __forceinline__ void whole_stage_tile(const Rows& rows, const ColumnBlock& b, int K,
                                                  const float* __restrict__ loss, float* pbest_loss,
                                                  Selection* sel, const MoveParams& m,
                                                  float* gbest_loss, long long c, unsigned* tickets) {
@@ -817,10 +835,10 @@ __device__ __forceinline__ void whole_stage_tile(const ColumnBlock& b, int K,
 
     const bool whole = c >= 0 && c + 4 <= b.n;
     int i = w;   // W <= K: every wavefront has a first particle
-    long long row = (long long)i * b.ld;
-    f32x4 xq = load_quad<kStageNT>(b.x + row, c, b.n, whole);
-    f32x4 vq = load_quad<kStageNT>(b.v + row, c, b.n, whole);
-    f32x4 pq = load_quad<kStageNT>(b.pbest + row, c, b.n, whole);
+    RowPtrs r = rows.row(i);
+    f32x4 xq = load_quad<kStageNT>(r.x, c, b.n, whole);
+    f32x4 vq = load_quad<kStageNT>(r.v, c, b.n, whole);
+    f32x4 pq = load_quad<kStageNT>(r.pbest, c, b.n, whole);
 
     // Algorithm 3: first argmin with NaN read as +inf (every lane gets the
     // result); Algorithm 1: the strict "<" test, false if either side is NaN
@@ -837,11 +855,11 @@ __device__ __forceinline__ void whole_stage_tile(const ColumnBlock& b, int K,
 
     // gbest for these columns: x_g before anybody moves, or the kept historical gbest
     const f32x4 gb =
-        load_quad<kStageNT>(replace ? b.x + (long long)g * b.ld : b.gbest, c, b.n, whole);
+        load_quad<kStageNT>(replace ? rows.row(g).x : b.gbest, c, b.n, whole);
     const long long d = (long long)b.d0 + c;   // may be negative in the first tile: see fused_tile
     const uint32_t pair = (uint32_t)(d >> 1);
-    RandomFour r = draw_four<ODD>(pair, (uint32_t)i, m);
-    asm volatile("" : "+v"(xq), "+v"(vq), "+v"(pq) : "v"(r.a.s0), "v"(r.b.s0), "v"(r.c.s0));
+    RandomFour rnd = draw_four<ODD>(pair, (uint32_t)i, m);
+    asm volatile("" : "+v"(xq), "+v"(vq), "+v"(pq) : "v"(rnd.a.s0), "v"(rnd.b.s0), "v"(rnd.c.s0));
     __syncthreads();   // every load above has returned, in every wavefront
 
     // (drawing the ticket earlier, under a barrier of its own right after the
@@ -853,17 +871,17 @@ __device__ __forceinline__ void whole_stage_tile(const ColumnBlock& b, int K,
     for (;;) {
         const bool improved = (improved_mask >> i) & 1ull;
         const f32x4 x_old = xq;
-        move_four<ODD>(xq, vq, improved ? x_old : pq, gb, r, m);
-        store_quad<kStageNT>(b.x + row, c, b.n, whole, xq);
-        store_quad<kStageNT>(b.v + row, c, b.n, whole, vq);
-        if (improved) store_quad<kStageNT>(b.pbest + row, c, b.n, whole, x_old);
+        move_four<ODD>(xq, vq, improved ? x_old : pq, gb, rnd, m);
+        store_quad<kStageNT>(r.x, c, b.n, whole, xq);
+        store_quad<kStageNT>(r.v, c, b.n, whole, vq);
+        if (improved) store_quad<kStageNT>(r.pbest, c, b.n, whole, x_old);
         i += W;
         if (i >= K) break;
-        row = (long long)i * b.ld;
-        xq = load_quad<kStageNT>(b.x + row, c, b.n, whole);
-        vq = load_quad<kStageNT>(b.v + row, c, b.n, whole);
-        if (!((improved_mask >> i) & 1ull)) pq = load_quad<kStageNT>(b.pbest + row, c, b.n, whole);
-        r = draw_four<ODD>(pair, (uint32_t)i, m);
+        r = rows.row(i);
+        xq = load_quad<kStageNT>(r.x, c, b.n, whole);
+        vq = load_quad<kStageNT>(r.v, c, b.n, whole);
+        if (!((improved_mask >> i) & 1ull)) pq = load_quad<kStageNT>(r.pbest, c, b.n, whole);
+        rnd = draw_four<ODD>(pair, (uint32_t)i, m);
     }
 
     if (threadIdx.x != 0) return;
@@ -893,10 +911,62 @@ __global__ __launch_bounds__(64 * kStageWaves) void whole_stage_kernel(
     const long long phase = (long long)((reinterpret_cast<uintptr_t>(b.x) >> 2) & (kStageTile - 1u));
     const long long c =
         (long long)blockIdx.x * kStageTile - phase + 4 * (long long)(threadIdx.x & 63);
+    const StackedRows rows{b.x, b.v, b.pbest, b.ld};
     if (((unsigned long long)phase + b.d0) & 1ull)
-        whole_stage_tile<true>(b, K, loss, pbest_loss, sel, m, gbest_loss, c, tickets);
+        whole_stage_tile<true>(rows, b, K, loss, pbest_loss, sel, m, gbest_loss, c, tickets);
     else
-        whole_stage_tile<false>(b, K, loss, pbest_loss, sel, m, gbest_loss, c, tickets);
+        whole_stage_tile<false>(rows, b, K, loss, pbest_loss, sel, m, gbest_loss, c, tickets);
+}
+
+// The same for the ragged layout, when all its segments fit one launch: a
+// workgroup owns 256 columns of one segment.  The tickets are drawn over the
+// whole launch, so pbest_loss is written when every segment's workgroups have
+// read it.
+struct StageEntry {
+    float* x;
+    float* v;
+    float* pbest;
+    float* gbest;
+    long long n;
+    unsigned long long d0;
+    unsigned first_wg;
+    unsigned reserved;
+};
+struct StageTable {
+    unsigned first_wg[kTableSegs];
+    StageEntry seg[kTableSegs];
+    int count;
+};
+
+__global__ __launch_bounds__(64 * kStageWaves) void whole_stage_segments_kernel(
+    StageTable tab, int K, const float* __restrict__ loss, float* pbest_loss, Selection* sel,
+    MoveParams m, float* gbest_loss, unsigned* tickets) {
+    const StageEntry& e = segment_of(tab, blockIdx.x);
+    const ColumnBlock b{e.x, e.v, e.pbest, e.gbest, e.n, e.n, e.d0};   // dense: row stride = n
+    const long long phase = (long long)((reinterpret_cast<uintptr_t>(b.x) >> 2) & (kStageTile - 1u));
+    const long long c = (long long)(blockIdx.x - e.first_wg) * kStageTile - phase +
+                        4 * (long long)(threadIdx.x & 63);
+    const StackedRows rows{b.x, b.v, b.pbest, b.ld};
+    if (((unsigned long long)phase + b.d0) & 1ull)
+        whole_stage_tile<true>(rows, b, K, loss, pbest_loss, sel, m, gbest_loss, c, tickets);
+    else
+        whole_stage_tile<false>(rows, b, K, loss, pbest_loss, sel, m, gbest_loss, c, tickets);
+}
+
+// The same for K <= kTableRows separate particle arrays (row-pointer mode).
+__global__ __launch_bounds__(64 * kStageWaves) void whole_stage_rows_kernel(
+    TableRows rows, float* gbest, long long n, int K, const float* __restrict__ loss,
+    float* pbest_loss, Selection* sel, MoveParams m, float* gbest_loss, unsigned* tickets) {
+    const ColumnBlock b{nullptr, nullptr, nullptr, gbest, 0, n, 0ull};   // gbest, n, d0 are used
+    // tiles are aligned to the address of particle 0's x
+    const long long phase =
+        (long long)((reinterpret_cast<uintptr_t>(rows.tab.x[0]) >> 2) & (kStageTile - 1u));
+    const long long c =
+        (long long)blockIdx.x * kStageTile - phase + 4 * (long long)(threadIdx.x & 63);
+    if ((unsigned long long)phase & 1ull)
+        whole_stage_tile<true>(rows, b, K, loss, pbest_loss, sel, m, gbest_loss, c, tickets);
+    else
+        whole_stage_tile<false>(rows, b, K, loss, pbest_loss, sel, m, gbest_loss, c, tickets);
 }
 
 // Parameter averaging (Section II-B, step 5) on the stacked layout, first half:
@@ -1394,6 +1464,38 @@ int enqueue_whole_stage(pso_ps_ctx* h, const ColumnBlock& b, float* pbest_loss, 
     return PSO_PS_OK;
 }
 
+// The ragged stage as one launch: every segment of `blocks` (at most kTableSegs).
+int enqueue_whole_stage_segments(pso_ps_ctx* h, const std::vector<ColumnBlock>& blocks,
+                                 float* pbest_loss, const float* loss, const MoveParams& m,
+                                 float* gbest_loss, hipStream_t stream) {
+    StageTable tab;
+    tab.count = (int)blocks.size();
+    unsigned long long wgs = 0;
+    for (int s = 0; s < kTableSegs; ++s) {
+        StageEntry& e = tab.seg[s];
+        if (s >= tab.count) {
+            e = tab.seg[tab.count - 1];  // never selected: segment_of stops at count
+            tab.first_wg[s] = 0xffffffffu;
+            continue;
+        }
+        const ColumnBlock& b = blocks[(size_t)s];
+        e.x = b.x; e.v = b.v; e.pbest = b.pbest; e.gbest = b.gbest;
+        e.n = b.n; e.d0 = b.d0; e.reserved = 0;
+        e.first_wg = tab.first_wg[s] = (unsigned)wgs;
+        const unsigned long long phase = (reinterpret_cast<uintptr_t>(b.x) >> 2) & (kStageTile - 1u);
+        wgs += (phase + (unsigned long long)b.n + kStageTile - 1u) / kStageTile;
+        if (wgs >= (1ull << 31)) return hip_fail(h, hipErrorInvalidConfiguration);
+    }
+    const int waves = h->K < kStageWaves ? h->K : kStageWaves;
+    hipLaunchKernelGGL(whole_stage_segments_kernel, dim3((unsigned)wgs), dim3(64u * (unsigned)waves), 0,
+                       stream, tab, h->K, loss, pbest_loss, h->sel, m, gbest_loss, h->tickets);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(h, e);
+    h->last_stream = stream;
+    h->have_selection = true;
+    return PSO_PS_OK;
+}
+
 MoveParams make_params(float w, float c1, float c2, uint64_t seed, uint64_t step) {
     MoveParams m;
     m.w = w; m.c1 = c1; m.c2 = c2;
@@ -1484,6 +1586,8 @@ int sync_segments(pso_ps_ctx* h, float* const* x_seg, float* const* v_seg, float
     }
     DeviceScope scope(h->device);
     if (scope.err != hipSuccess) return hip_fail(h, scope.err);
+    if (single_launch_chosen(h) && !blocks.empty() && blocks.size() <= (size_t)kTableSegs)
+        return enqueue_whole_stage_segments(h, blocks, pbest_loss, loss, m, gbest_loss, stream);
     const int block = block_of(h);
     const bool vec = vector_path(h);
     // Up to kTableSegs segments per launch; the selection rides on the first
@@ -1574,6 +1678,26 @@ int sync_rows(pso_ps_ctx* h, float* const* x_rows, float* const* v_rows, float* 
     DeviceScope scope(h->device);
     if (scope.err != hipSuccess) return hip_fail(h, scope.err);
     const long long n = (long long)h->D;
+    if (single_launch_chosen(h)) {   // implies K <= kTableRows
+        TableRows rows;
+        for (int i = 0; i < kTableRows; ++i) {
+            rows.tab.x[i] = (i < h->K) ? x_rows[i] : nullptr;
+            rows.tab.v[i] = (i < h->K) ? v_rows[i] : nullptr;
+            rows.tab.pbest[i] = (i < h->K) ? pbest_rows[i] : nullptr;
+        }
+        const unsigned long long phase = (reinterpret_cast<uintptr_t>(x_rows[0]) >> 2) & (kStageTile - 1u);
+        const unsigned long long grid = (phase + (unsigned long long)n + kStageTile - 1u) / kStageTile;
+        if (grid >= (1ull << 31)) return hip_fail(h, hipErrorInvalidConfiguration);
+        const int waves = h->K < kStageWaves ? h->K : kStageWaves;
+        hipLaunchKernelGGL(whole_stage_rows_kernel, dim3((unsigned)grid), dim3(64u * (unsigned)waves), 0,
+                           stream, rows, gbest, n, h->K, loss, pbest_loss, h->sel, m, gbest_loss,
+                           h->tickets);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail(h, e);
+        h->last_stream = stream;
+        h->have_selection = true;
+        return PSO_PS_OK;
+    }
     // gbest copies first (each launch carries up to kTableRows row pointers and
     // copies only if g is among them), then the updates.
     for (int row0 = 0; row0 < h->K; row0 += kTableRows) {

@@ -39,7 +39,7 @@ def test_config_trajectory_padded_rows(oracle, name, stage_launches):
     run_trajectory(oracle, wl.make_swarm(cfg, ld=ld), steps=min(cfg.steps, 6))
 
 
-def test_lenet5_segments_match_flat_and_oracle(oracle):
+def test_lenet5_segments_match_flat_and_oracle(oracle, stage_launches):
     """The ragged per-layer layout gives the bits of the flat layout."""
     cfg = wl.CONFIGS["lenet5"]
     print(f"[case] config lenet5, {len(cfg.segments)} segments", flush=True)
@@ -51,10 +51,13 @@ def test_lenet5_segments_match_flat_and_oracle(oracle):
     dg = [torch.zeros(n, dtype=torch.float32, device=gh.dev()) for n in sizes]
     dpl = gh.to_dev(sw.pbest_loss)
     h = pso.pso_ps_create(cfg.K, cfg.D, cfg.D, seg_sizes=sizes)
+    tables = [pso.pso_ps_pointer_table(t) for t in (dx, dv, dp, dg)]
     try:
         for s in range(cfg.steps):
             w, c1, c2 = float(sw.w[s]), float(sw.c1), float(sw.c2)
-            pso.pso_ps_sync_segments(h, dx, dv, dp, dpl, gh.to_dev(sw.losses[s]), dg,
+            # lists of tensors, or pointer tables marshalled once: the same call
+            a = (dx, dv, dp, dg) if s % 2 == 0 else tables
+            pso.pso_ps_sync_segments(h, a[0], a[1], a[2], dpl, gh.to_dev(sw.losses[s]), a[3],
                                      w, c1, c2, cfg.seed, s)
             g, improved = oracle.sync(hx, hv, hp, hpl, sw.losses[s], hg, F32(w), F32(c1), F32(c2),
                                       cfg.seed, s)
@@ -76,7 +79,7 @@ def test_lenet5_segments_match_flat_and_oracle(oracle):
     # more segments than one launch carries, ResNet-like: many small tensors and a few large ones
     [64, 64, 1728, 64, 64] * 14 + [0, 36_864, 1, 73_728, 128, 128, 10],
 ])
-def test_odd_and_empty_segments(oracle, sizes):
+def test_odd_and_empty_segments(oracle, sizes, stage_launches):
     """Segment sizes that are odd (a Philox pair straddles two segments),
     one, and zero; several launches' worth of segments."""
     K, D = 5, sum(sizes)

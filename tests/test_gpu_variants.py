@@ -143,7 +143,7 @@ def test_single_pass_variant(oracle, fused_rows, block, K, D, ld, offset):
     (33, 1_030, [2 * (i % 2) for i in range(33)]),
     (65, 1_030, [2 * (i % 2) for i in range(65)]),
 ])
-def test_row_pointer_mode(oracle, K, D, offsets):
+def test_row_pointer_mode(oracle, K, D, offsets, stage_launches):
     print(f"[case] row pointers K={K} D={D} offsets={offsets[:6]}", flush=True)
     sw = wl.small_swarm(K, D, seed=41 + K, steps=3)
     if K >= 65:
@@ -172,7 +172,7 @@ def test_row_pointer_mode(oracle, K, D, offsets):
     (5, 20_002, [0, 2, 1, 3, 0]),              # every alignment among the rows
     (70, 3_001, [i % 4 for i in range(70)]),   # two launches of row pointers, g moves between them
 ])
-def test_row_pointer_mode_with_history(oracle, K, D, offsets):
+def test_row_pointer_mode_with_history(oracle, K, D, offsets, stage_launches):
     print(f"[case] row pointers + historical gBest K={K} D={D}", flush=True)
     steps = 6
     sw = wl.small_swarm(K, D, seed=43 + K, steps=steps)
@@ -211,7 +211,7 @@ def test_row_pointer_mode_with_history(oracle, K, D, offsets):
     list(wl.LENET5_SEGMENTS),
     [64, 63, 1728, 1, 64] * 14 + [0, 36_864, 1, 73_729, 128, 127, 10],   # three launches, odd starts
 ])
-def test_segments_with_history(oracle, sizes):
+def test_segments_with_history(oracle, sizes, stage_launches):
     K, D, steps = 6, sum(sizes), 6
     print(f"[case] segments + historical gBest K={K} D={D} in {len(sizes)} segments", flush=True)
     sw = wl.small_swarm(K, D, seed=47, steps=steps)
