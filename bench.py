@@ -242,7 +242,8 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="resnet50x32")
+    ap.add_argument("--workload", default="resnet50x32",
+                    help="a named configuration, or KxD (e.g. 8x250000) for a swarm of that shape")
     ap.add_argument("--block", type=int, default=0, help="threads per workgroup (0 = default)")
     ap.add_argument("--super-tiles", type=int, default=0)
     ap.add_argument("--chunk-tiles", type=int, default=0)
@@ -303,7 +304,13 @@ def main() -> int:
         return 3
     if args.variant == "stream":
         return stream_probe(args)
-    cfg = wl.CONFIGS[args.workload]
+    if "x" in args.workload and args.workload.replace("x", "").isdigit():
+        # "KxD": a swarm of that shape with resnet20's value distributions (for size sweeps)
+        k_arg, d_arg = (int(t) for t in args.workload.split("x"))
+        cfg = wl.SwarmConfig(**{**wl.CONFIGS["resnet20"].__dict__, "name": args.workload,
+                                "K": k_arg, "D": d_arg})
+    else:
+        cfg = wl.CONFIGS[args.workload]
     K, D = cfg.K, cfg.D
     dev = torch.device("cuda:0")
     total = args.warmup + 3 * args.steps            # the timed pass, the per-kernel pass and
@@ -442,7 +449,7 @@ def main() -> int:
                   "segments": "select_gbest_segments_kernel + update_segments_kernel",
                   "history": "select_gbest_kernel + update_kernel"}[args.variant]
     stage_gbs = stage_bytes / (stage_t["avg"] * 1e-3) / 1e9
-    fits_one = args.variant in ("sync", "history") or (
+    fits_one = args.variant in ("sync", "history", "rows") or (
         args.variant == "segments" and sum(1 for n in cfg.segments if n > 0) <= 32)
     one_launch = fits_one and not args.fused_rows and (
         args.single_launch == 1 or (args.single_launch < 0 and K <= 16
