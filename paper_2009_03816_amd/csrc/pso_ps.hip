@@ -1,7 +1,7 @@
 // PSO-PS synchronization step for gfx950 (MI355X): HIP kernels and the C ABI
 // declared in include/pso_ps.h.
 //
-// Two kernels per stage.  Flat layout without history (pso_ps_sync):
+// Two kernels per stage of a large swarm.  Flat layout without history (pso_ps_sync):
 //   select_move_best_kernel  g = argmin loss (Algorithm 3), improved_i = loss_i <
 //                        pbest_loss_i (Algorithm 1), and the move of the best
 //                        particle itself (Eq. (6), (7)), which stores gbest =
@@ -15,6 +15,12 @@
 //                        (TableSource / select_gbest_segments_kernel variants),
 //   update_kernel        the pass over all K rows (update_rows_kernel,
 //                        update_segments_kernel).
+// A small swarm (K <= 16, K * D <= 750,000; more on request) takes the whole
+// stage in ONE launch instead, because two dependent launches are what it
+// pays for: whole_stage_kernel (and its ragged and row-pointer forms), one
+// wavefront per particle, a workgroup barrier between everybody's read of x_g
+// and its owner's write, and ticket counters that tell the last workgroup it
+// may write pbest_loss.
 // Parameter averaging, the synchronization the method replaces, is
 // mean_kernel + broadcast_kernel.  fused_rows_kernel is the stage as a single
 // pass (one workgroup owns a tile of columns for all K rows and keeps its piece
