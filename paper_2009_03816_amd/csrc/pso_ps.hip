@@ -721,7 +721,6 @@ __device__ __forceinline__ void fused_tile(const ColumnBlock& b, int K,
     const uint32_t pair = (uint32_t)(d >> 1);
 
     f32x4 xq[P], vq[P], pq[P];
-    unsigned long long mask = 0;
     auto improved_bit = [&](int i) { return (sel->improved[i >> 6] >> (i & 63)) & 1ull; };
     auto fetch = [&](int i, f32x4& xo, f32x4& vo, f32x4& po) {
         const long long row = (long long)i * b.ld;
@@ -733,7 +732,6 @@ __device__ __forceinline__ void fused_tile(const ColumnBlock& b, int K,
 #pragma unroll
     for (int s = 0; s < P; ++s)
         if (s < K) fetch(s, xq[s], vq[s], pq[s]);
-    (void)mask;
 
     for (int base = 0; base < K; base += P) {
 #pragma unroll
