@@ -115,9 +115,22 @@ def stream_probe(args) -> int:
                  nt_stores=bool(args.probe_nt_stores),
                  absolute_chunks=args.probe_absolute_chunks)
 
+    kernel_name = "stream_kernel"
+    if args.probe_policy:
+        # the in-place mix in its default shape with explicit cache-policy bits
+        loads, stores = (probes.policy_bits(t) for t in args.probe_policy.split(","))
+        assert args.probe_mix == "inplace" and block == 64 and args.probe_quads == 1
+        shape = dict(super_tiles=shape["super_tiles"], chunk_tiles=shape["chunk_tiles"],
+                     wgs_per_cu=shape["wgs_per_cu"], load_policy=loads, store_policy=stores)
+        kernel_name = "policy_kernel"
+
     def stage(_):
-        probes.pso_ps_probe_stream(args.probe_mix, x, v, p, sink, K, D, ld,
-                                   stream=int(stream.cuda_stream), **shape)
+        if args.probe_policy:
+            probes.pso_ps_probe_policy(x, v, p, sink, K, D, ld, stream=int(stream.cuda_stream),
+                                       **shape)
+        else:
+            probes.pso_ps_probe_stream(args.probe_mix, x, v, p, sink, K, D, ld,
+                                       stream=int(stream.cuda_stream), **shape)
 
     for s in range(args.warmup):
         stage(s)
@@ -135,7 +148,7 @@ def stream_probe(args) -> int:
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: K={K} x D={D} fp32, row stride {ld}",
                    "variant": "stream", "mix": args.probe_mix, **shape},
-        "roofline": {"bound": "hbm", "kernel": "stream_kernel", "achieved": gbs,
+        "roofline": {"bound": "hbm", "kernel": kernel_name, "achieved": gbs,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
                      "traffic": None, "algorithmic_bytes_per_launch": nbytes,
                      "kernel_ms_avg": t["avg"], "kernel_ms_median": t["median"],
@@ -282,8 +295,11 @@ def main() -> int:
     ap.add_argument("--probe-nt-loads", type=int, default=1)
     ap.add_argument("--probe-nt-stores", type=int, default=1)
     ap.add_argument("--probe-absolute-chunks", type=int, default=0)
+    ap.add_argument("--probe-policy", default="",
+                    help="--variant stream: LOADS,STORES cache-policy bits for the in-place mix in "
+                         "its default shape, each a sum of sc0, nt, sc1 or none (e.g. nt,nt+sc1)")
     ap.add_argument("--graph", action="store_true",
-                    help="also capture ten stages into a HIP graph, replay it and report the time "
+                    help="also capture 100 stages into a HIP graph, replay it and report the time "
                          "per stage (roofline.stage.hip_graph_replay_ms)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",

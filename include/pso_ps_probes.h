@@ -47,6 +47,16 @@ int pso_ps_probe_stream(int mix, float* x, float* v, float* pbest, float* sink, 
                         int chunked, int super_tiles, int chunk_tiles, int wgs_per_cu,
                         int nt_loads, int nt_stores, int absolute_chunks, void* hip_stream);
 
+/* The in-place mix of pso_ps_probe_stream (mix 2) in its default shape (64
+ * threads, one 128-bit access per thread and array, XCD-aware order) with the
+ * cache-policy bits of the loads and of the stores chosen freely: 0 none,
+ * 1 sc0, 2 nt (what "non-temporal" compiles to), 16 sc1, and the sums 3, 17, 18,
+ * 19.  A row must be shorter than 4 GiB.  Same alignment rules and return
+ * codes. */
+int pso_ps_probe_policy(float* x, float* v, float* pbest, float* sink, int K, int64_t D,
+                        int64_t ld, int super_tiles, int chunk_tiles, int wgs_per_cu,
+                        int load_policy, int store_policy, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -127,6 +127,67 @@ hipError_t launch_mix(int mix, int ntl, int nts, dim3 grid, unsigned lds, hipStr
     }
 }
 
+// The in-place mix (read x, v, pbest; write x, v back) with the cache-policy
+// bits of the accesses chosen freely: 64 threads, one 128-bit access per thread
+// and array, XCD-aware order.  Raw buffer loads and stores carry the bits as
+// an immediate (sc0 = 1, nt = 2, sc1 = 16 and their sums); the buffer spans one
+// row, so an access outside it would be dropped by the hardware.
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+
+template <int LOADS, int STORES>
+__global__ __launch_bounds__(64) void policy_kernel(StreamArgs a, float* sink) {
+    constexpr unsigned TILE = 256;
+    unsigned row, tile;
+    if (!decode_tile_order(a.ord, (unsigned)a.rows, blockIdx.x, &row, &tile)) return;
+    float* x = a.x + (long long)row * a.ld;
+    float* v = a.v + (long long)row * a.ld;
+    float* p = a.p + (long long)row * a.ld;
+    const long long phase = (long long)((reinterpret_cast<uintptr_t>(x) >> 2) & (TILE - 1u));
+    const long long c = (long long)tile * TILE - phase + 4 * (long long)threadIdx.x;
+    if (c < 0 || c + 4 > a.n) return;   // the ragged ends of a row are skipped: a probe
+    const unsigned bytes = (unsigned)(a.n * 4);
+    const unsigned off = (unsigned)(c * 4);
+    constexpr int kRsrcFlags = 0x00020000;   // raw 32-bit data, no swizzle
+    __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(x, 0, bytes, kRsrcFlags);
+    __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc(v, 0, bytes, kRsrcFlags);
+    __amdgpu_buffer_rsrc_t rp = __builtin_amdgcn_make_buffer_rsrc(p, 0, bytes, kRsrcFlags);
+    const u32x4 xq = __builtin_amdgcn_raw_buffer_load_b128(rx, off, 0, LOADS);
+    const u32x4 vq = __builtin_amdgcn_raw_buffer_load_b128(rv, off, 0, LOADS);
+    const u32x4 pq = __builtin_amdgcn_raw_buffer_load_b128(rp, off, 0, LOADS);
+    if (pq.x == 0x7f123456u && pq.y == 0x7f654321u) *sink = (float)pq.z;   // keeps the load alive
+    __builtin_amdgcn_raw_buffer_store_b128(xq, rx, off, 0, STORES);
+    __builtin_amdgcn_raw_buffer_store_b128(vq, rv, off, 0, STORES);
+}
+
+typedef void (*PolicyKernel)(StreamArgs, float*);
+template <int LOADS>
+PolicyKernel policy_for_stores(int stores) {
+    switch (stores) {
+        case 0: return policy_kernel<LOADS, 0>;
+        case 1: return policy_kernel<LOADS, 1>;
+        case 2: return policy_kernel<LOADS, 2>;
+        case 3: return policy_kernel<LOADS, 3>;
+        case 16: return policy_kernel<LOADS, 16>;
+        case 17: return policy_kernel<LOADS, 17>;
+        case 18: return policy_kernel<LOADS, 18>;
+        case 19: return policy_kernel<LOADS, 19>;
+        default: return nullptr;
+    }
+}
+PolicyKernel policy_for(int loads, int stores) {
+    switch (loads) {
+        case 0: return policy_for_stores<0>(stores);
+        case 1: return policy_for_stores<1>(stores);
+        case 2: return policy_for_stores<2>(stores);
+        case 3: return policy_for_stores<3>(stores);
+        case 16: return policy_for_stores<16>(stores);
+        case 17: return policy_for_stores<17>(stores);
+        case 18: return policy_for_stores<18>(stores);
+        case 19: return policy_for_stores<19>(stores);
+        default: return nullptr;
+    }
+}
+
 }  // namespace
 
 extern "C" int pso_ps_probe_stream(int mix, float* x, float* v, float* pbest, float* sink, int K,
@@ -179,4 +240,38 @@ extern "C" int pso_ps_probe_stream(int mix, float* x, float* v, float* pbest, fl
     else e = quads == 1 ? PROBE(256, 1) : PROBE(256, 2);
 #undef PROBE
     return e == hipSuccess ? 0 : -3;
+}
+
+extern "C" int pso_ps_probe_policy(float* x, float* v, float* pbest, float* sink, int K, int64_t D,
+                                   int64_t ld, int super_tiles, int chunk_tiles, int wgs_per_cu,
+                                   int load_policy, int store_policy, void* hip_stream) {
+    if (!x || !v || !pbest || !sink || K < 1 || D < 4 || ld < D) return -1;
+    if ((uint64_t)D * 4u >= (1ull << 32)) return -1;   // a row must fit one buffer descriptor
+    if (super_tiles < 1 || chunk_tiles < 1 || (super_tiles & (super_tiles - 1)) ||
+        (chunk_tiles & (chunk_tiles - 1)))
+        return -1;
+    const PolicyKernel kernel = policy_for(load_policy, store_policy);
+    if (!kernel) return -1;
+    if ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(v) |
+         reinterpret_cast<uintptr_t>(pbest)) & 15u)
+        return -2;
+    if (K > 1 && (ld & 3)) return -2;
+    StreamArgs a{x, v, pbest, (long long)ld, (long long)D, K, 1, 1, 0, {}};
+    unsigned long long max_phase = 0;
+    for (int i = 0; i < K; ++i) {
+        const unsigned long long ph = (reinterpret_cast<uintptr_t>(x + (long long)i * ld) >> 2) & 255u;
+        if (ph > max_phase) max_phase = ph;
+    }
+    const unsigned long long tiles = (max_phase + (unsigned long long)D + 255u) / 256u;
+    unsigned long long grid = 0;
+    if (!plan_tile_order(K, tiles, (unsigned long long)super_tiles, (unsigned long long)chunk_tiles,
+                         &a.ord, &grid) || grid >= (1ull << 31))
+        return -1;
+    unsigned lds = 0;
+    if (wgs_per_cu >= 3 && wgs_per_cu < 64) {
+        lds = (160u * 1024u / (unsigned)wgs_per_cu) & ~511u;
+        if (lds > 64u * 1024u) lds = 64u * 1024u;
+    }
+    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(64), lds, (hipStream_t)hip_stream, a, sink);
+    return hipGetLastError() == hipSuccess ? 0 : -3;
 }

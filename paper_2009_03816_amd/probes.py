@@ -22,6 +22,8 @@ def load():
         P, I, I64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
         lib.pso_ps_probe_stream.argtypes = [I, P, P, P, P, I, I64, I64, I, I, I, I, I, I, I, I, I, I, P]
         lib.pso_ps_probe_stream.restype = I
+        lib.pso_ps_probe_policy.argtypes = [P, P, P, P, I, I64, I64, I, I, I, I, I, P]
+        lib.pso_ps_probe_policy.restype = I
         _lib = lib
     return _lib
 
@@ -41,3 +43,21 @@ def pso_ps_probe_stream(mix: str, x, v, pbest, sink, K: int, D: int, ld: int, bl
                                     stream or None)
     if rc != 0:
         raise RuntimeError(f"pso_ps_probe_stream: status {rc}")
+
+
+POLICY_BITS = {"sc0": 1, "nt": 2, "sc1": 16}
+
+
+def policy_bits(text: str) -> int:
+    """'nt+sc1' -> 18; 'none' or '' -> 0."""
+    return sum(POLICY_BITS[t] for t in text.split("+") if t and t != "none")
+
+
+def pso_ps_probe_policy(x, v, pbest, sink, K: int, D: int, ld: int, super_tiles: int = 2048,
+                        chunk_tiles: int = 256, wgs_per_cu: int = 20, load_policy: int = 2,
+                        store_policy: int = 2, stream: int = 0) -> None:
+    rc = load().pso_ps_probe_policy(x.data_ptr(), v.data_ptr(), pbest.data_ptr(), sink.data_ptr(),
+                                    K, D, ld, super_tiles, chunk_tiles, wgs_per_cu, load_policy,
+                                    store_policy, stream or None)
+    if rc != 0:
+        raise RuntimeError(f"pso_ps_probe_policy: status {rc}")

@@ -60,7 +60,7 @@ def test_probe_library_exports_what_its_header_declares():
     text = open(os.path.join(ROOT, "include", "pso_ps_probes.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = sorted(set(re.findall(r"\b(pso_ps_[a-z_]+)\s*\(", text)))
-    assert names == ["pso_ps_probe_stream"]
+    assert names == ["pso_ps_probe_policy", "pso_ps_probe_stream"]
     if not os.path.exists(build.PROBES_LIBRARY):
         build.build_probes()
     lib = ctypes.CDLL(build.PROBES_LIBRARY)
@@ -69,3 +69,4 @@ def test_probe_library_exports_what_its_header_declares():
     # rejected before any HIP call is made
     assert lib.pso_ps_probe_stream(2, None, None, None, None, 4, 16, 16, 128, 1, 1, 1, 1024, 128,
                                    10, 1, 1, 0, None) == -1
+    assert lib.pso_ps_probe_policy(None, None, None, None, 4, 16, 16, 2048, 256, 20, 2, 2, None) == -1
