@@ -32,7 +32,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 MEASURED_TRAFFIC = {
     # profiles/update_others_kernel_resnet50x32_hbm_traffic.md: update_others_kernel, mean of the
     # three timed launches
-    ("resnet50x32", "208da45cad2b4182"): 15948642000.0,
+    ("resnet50x32", "682a378094ddd28a"): 16153050000.0,
 }
 
 # What arithmetic-free streams over the same kind of arrays reached on one MI355X
