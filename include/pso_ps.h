@@ -237,7 +237,9 @@ int pso_ps_last_selection(pso_ps_ctx* h, int* g_out, uint64_t* improved_mask_out
  *                  wavefronts per compute unit
  *   force_generic  != 0: element-wise path instead of the 128-bit one
  * The gbest copy of a stage has a fixed shape of its own (256 threads, 16 KiB
- * per workgroup) and follows only the chunk and super-chunk sizes, in bytes. */
+ * per workgroup) and follows only the chunk and super-chunk sizes, in bytes.
+ * All of this concerns the stage in two launches; the single-launch stage that
+ * small swarms take (pso_ps_set_single_launch) has one fixed shape. */
 int pso_ps_set_launch(pso_ps_ctx* h, int block_threads, int super_tiles, int chunk_tiles,
                       int wgs_per_cu, int force_generic);
 
@@ -264,7 +266,8 @@ int pso_ps_set_launch(pso_ps_ctx* h, int block_threads, int super_tiles, int chu
  *                   multiples of the run size in memory, run j of memory going
  *                   to XCD j mod 8; 2 at absolute multiples of the run size,
  *                   the first run of every row going to XCD 0.
- * The ragged and row-pointer entry points ignore all three. */
+ * The ragged and row-pointer entry points ignore all three, and so does the
+ * single-launch stage, except that fused_rows > 0 takes precedence over it. */
 int pso_ps_set_variant(pso_ps_ctx* h, int fused_rows, int chunk_origin, int best_first);
 
 /* Whether pso_ps_sync, pso_ps_sync_history, the ragged and the row-pointer
