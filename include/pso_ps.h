@@ -76,7 +76,7 @@ extern "C" {
 #define PSO_PS_SINGLE_LAUNCH_MAX_K 64  /* largest swarm the single-launch stage takes */
 /* K * D up to which pso_ps_sync and pso_ps_sync_history choose the
  * single-launch stage by themselves (for K <= 16) */
-#define PSO_PS_SINGLE_LAUNCH_MAX_PARAMS 750000
+#define PSO_PS_SINGLE_LAUNCH_MAX_PARAMS 1000000
 
 typedef struct pso_ps_ctx pso_ps_ctx;
 

@@ -19,7 +19,7 @@ PSO_PS_ENOMEM = -4
 PSO_PS_ELIMIT = -5
 PSO_PS_STATIC_MAX_K = 4096
 PSO_PS_SINGLE_LAUNCH_MAX_K = 64
-PSO_PS_SINGLE_LAUNCH_MAX_PARAMS = 750_000
+PSO_PS_SINGLE_LAUNCH_MAX_PARAMS = 1_000_000
 
 _f32p = ctypes.c_void_p   # device addresses travel as plain pointers
 _lib = None

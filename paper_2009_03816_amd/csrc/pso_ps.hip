@@ -15,7 +15,7 @@
 //                        (TableSource / select_gbest_segments_kernel variants),
 //   update_kernel        the pass over all K rows (update_rows_kernel,
 //                        update_segments_kernel).
-// A small swarm (K <= 16, K * D <= 750,000; more on request) takes the whole
+// A small swarm (K <= 16, K * D <= 1,000,000; more on request) takes the whole
 // stage in ONE launch instead, because two dependent launches are what it
 // pays for: whole_stage_kernel (and its ragged and row-pointer forms), one
 // wavefront per particle, a workgroup barrier between everybody's read of x_g
