@@ -815,12 +815,6 @@ constexpr unsigned kTicketShards = 16;
 constexpr unsigned kTicketStride = 64;  // counters are 64 unsigned = 256 bytes apart
 constexpr size_t kTicketBytes = (size_t)(kTicketShards + 1) * kTicketStride * sizeof(unsigned);
 
-// Everything before the barrier is ordered for latency, which is all a small
-// swarm pays: the losses are requested first, then this wavefront's first
-// particle (pbest too, whether or not it turns out to be needed: waiting for
-// the "<" test would cost a round trip); the selection runs when the losses
-// are there; x_g can only be requested then; the random words are computed
-// while all of that is in flight.
 // `rows` says where particle i's x, v and pbest start (stacked with a stride,
 // or K separate arrays); `b` carries gbest, the number of columns and d0.
 struct StackedRows {
@@ -838,6 +832,12 @@ struct TableRows {
     __device__ RowPtrs row(int i) const { return RowPtrs{tab.x[i], tab.v[i], tab.pbest[i]}; }
 };
 
+// One tile of the single-launch stage.  Everything before the barrier is ordered for latency, which is all a small
+// swarm pays: the losses are requested first, then this wavefront's first
+// particle (pbest too, whether or not it turns out to be needed: waiting for
+// the "<" test would cost a round trip); the selection runs when the losses
+// are there; x_g can only be requested then; the random words are computed
+// while all of that is in flight.
 template <bool ODD, class Rows>
 __device__ __forceinline__ void whole_stage_tile(const Rows& rows, const ColumnBlock& b, int K,
                                                  const float* __restrict__ loss, float* pbest_loss,
