@@ -832,8 +832,9 @@ struct TableRows {
     __device__ RowPtrs row(int i) const { return RowPtrs{tab.x[i], tab.v[i], tab.pbest[i]}; }
 };
 
-// One tile of the single-launch stage.  Everything before the barrier is ordered for latency, which is all a small
-// swarm pays: the losses are requested first, then this wavefront's first
+// One tile of the single-launch stage.  Everything before the barrier is
+// ordered for latency, which is all a small swarm pays: the losses are
+// requested first, then this wavefront's first
 // particle (pbest too, whether or not it turns out to be needed: waiting for
 // the "<" test would cost a round trip); the selection runs when the losses
 // are there; x_g can only be requested then; the random words are computed
