@@ -165,7 +165,10 @@ int pso_ps_sync_rows_history(pso_ps_ctx* h, float* const* x_rows, float* const* 
  * caller; back-to-back calls on one stream are fine.  The array keeps the last
  * call's contents; every call rewrites all of it that it reads, and leaves the
  * ticket counters at zero, as it found them.  The stage takes one launch or
- * two as pso_ps_sync does by default (see pso_ps_set_single_launch). */
+ * two as pso_ps_sync does by default (see pso_ps_set_single_launch).  The
+ * first call on a device looks up the array's address on that GPU
+ * (hipGetSymbolAddress, once per device and process): a caller that captures
+ * into a HIP graph makes its first call on the device before the capture. */
 int pso_ps_sync_static(int device, int K, int64_t D, int64_t ld, float* x, float* v,
                        float* pbest, float* pbest_loss, const float* loss, float* gbest,
                        float w, float c1, float c2, uint64_t seed, uint64_t step,
