@@ -118,6 +118,7 @@ def test_odd_and_empty_segments(oracle, sizes, stage_launches):
     (5, 3000, 3000, 2),                      # buffers 8-byte aligned only
     (33, 1500, 1500, 0), (64, 260, 260, 0), (65, 260, 260, 0), (130, 132, 132, 0),   # K beyond a wave
     (7, 70_000, 70_000, 0),                  # several workgroups and a ragged last one
+    (40, 100_003, 100_003, 1),               # single launch: three particles per wavefront, 391 tiles
     # x, v, pbest and gbest at different offsets from a 16-byte boundary: 128-bit accesses
     # aligned in x only; odd offsets of x flip the parity of the random-number pairs
     (5, 3000, 3000, (0, 1, 2, 3)), (5, 3000, 3000, (1, 0, 3, 2)), (4, 5001, 5001, (3, 3, 0, 1)),
