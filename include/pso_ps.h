@@ -46,8 +46,9 @@
  *
  * Execution: the calls enqueue work on `hip_stream` (a hipStream_t passed as
  * void*, NULL = the default stream) and return without waiting; nothing is
- * allocated or copied to the host per call.  The handle owns a few bytes of
- * device scratch (g and the improved mask).  Calls on one handle must be
+ * allocated or copied to the host per call.  The handle owns a few KiB of
+ * device scratch (g, the improved mask, the ticket counters of the
+ * single-launch stage).  Calls on one handle must be
  * issued from one host thread at a time and on one stream at a time (work of
  * two stages on different streams would share the scratch).
  *
